@@ -1,0 +1,124 @@
+/*
+ * bsfa.h — C ABI of the MI355X (gfx950) Block-Sparse FlashAttention forward library, libbsfa.so.
+ *
+ * The library implements the prefill attention of the paper "Block Sparse Flash Attention"
+ * (Section 4 and Algorithm 1): tiled exact attention in which, for every query tile i
+ * (B_M rows) and key block j (B_N rows), the score tile S_ij = Q_i K_j^T / sqrt(d) (Eq. 5) is
+ * computed exactly, its maximum s_max (Eq. 6) is compared with a calibrated threshold, and a
+ * block with s_max < threshold is skipped: its V block is not loaded, no exponentials are
+ * taken, no P.V product is formed and the running softmax statistics are left untouched
+ * (Section 4.1).  Key blocks that touch the causal boundary bypass the gate (Section 4.1,
+ * last paragraph).  Equality keeps the block (Section 4.1 states the skip condition as a
+ * strict inequality).
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all
+ *    buffers; the library keeps no device memory between calls.
+ *  - Tensors are addressed through element strides; the head dimension is contiguous
+ *    (stride 1).  Strides must be multiples of 8 elements and base pointers 16-byte aligned.
+ *    [B, N, H, d] and [B, H, N, d] are both expressible.
+ *  - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *  - bsfa_forward only enqueues work on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and returns.  bsfa_calibrate synchronises that stream before it
+ *    returns because it writes host memory.
+ *  - On a validation error nothing is launched and no output is touched.  Functions return a
+ *    bsfa_status; bsfa_last_error() gives a thread-local message for the last failure.
+ *  - A NaN threshold gives undefined gate decisions (it is not detected).
+ */
+#ifndef BSFA_H
+#define BSFA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BSFA_OK = 0,
+    BSFA_ERR_NULL = -1,        /* a required pointer is NULL                              */
+    BSFA_ERR_SHAPE = -2,       /* sizes inconsistent, not tile aligned, bad stride/align  */
+    BSFA_ERR_DTYPE = -3,       /* element type not supported                              */
+    BSFA_ERR_UNSUPPORTED = -4, /* head_dim / tile shape the library was not built for     */
+    BSFA_ERR_WORKSPACE = -5,   /* workspace missing or too small                          */
+    BSFA_ERR_HIP = -6          /* a HIP runtime call failed (message in bsfa_last_error)  */
+} bsfa_status;
+
+typedef enum { BSFA_BF16 = 0 } bsfa_dtype; /* inputs/outputs bf16, fp32 accumulation */
+
+/* Problem descriptor (paper notation, Section 2.2: N tokens, head dim d, query tiles of B_M
+ * rows, key/value blocks of B_N rows).  seqlen must be a multiple of block_m and block_n. */
+typedef struct {
+    int32_t batch, n_q_heads, n_kv_heads, seqlen, head_dim;
+    int32_t block_m, block_n;     /* gate tile; see bsfa_query_build for the supported shapes */
+    int64_t q_stride_b, q_stride_n, q_stride_h;   /* element strides: batch, token, head */
+    int64_t k_stride_b, k_stride_n, k_stride_h;
+    int64_t v_stride_b, v_stride_n, v_stride_h;
+    int64_t o_stride_b, o_stride_n, o_stride_h;
+    int32_t dtype;                /* bsfa_dtype */
+    int32_t thresholds_per_tile;  /* 0: thresholds[n_q_heads] (one per head);
+                                     1: thresholds[n_q_heads][seqlen/block_m], the paper's
+                                        T_{l,h,i} for one layer and one sparsity level
+                                        (Section 4.2) */
+} bsfa_problem;
+
+/* Optional outputs of bsfa_forward; any member may be NULL.  All DEVICE, caller allocated.
+ * A key block is "reachable" for query tile i if causal masking leaves it any entry,
+ * "gateable" if it leaves it every entry (these are the blocks the gate applies to). */
+typedef struct {
+    uint64_t *counts;     /* [batch][n_q_heads][3] = tiles skipped, gateable, reachable; the
+                             measured density of Section 5.1 (Metrics) is 1 - skipped/reachable.
+                             Overwritten (not accumulated). */
+    uint32_t *skip_mask;  /* [batch][n_q_heads][M_Q][ceil(M_KV/32)], bit (j%32) of word j/32
+                             set iff block j was skipped for query tile i */
+    float    *block_max;  /* [batch][n_q_heads][M_Q][M_KV]: s_max (Eq. 6, natural score units,
+                             1/sqrt(d) included) of gateable blocks, NaN elsewhere */
+} bsfa_skip_stats;
+
+/*
+ * Forward pass (Algorithm 1 for every batch, head and query tile).
+ *   q [batch, seqlen, n_q_heads, d], k and v [batch, seqlen, n_kv_heads, d], out like q, all
+ *   through the strides in *p; thresholds: DEVICE fp32, natural score units.  -INFINITY
+ *   disables the gate (dense attention, same code path); +INFINITY keeps only the blocks that
+ *   bypass the gate.  causal != 0: causal mask; causal == 0: no mask, and the key blocks that
+ *   overlap the query tile's own token range bypass the gate (the paper only says the method
+ *   extends to the bidirectional case, Section 4.3; this keeps its "local blocks are always
+ *   processed" rule).
+ * Returns BSFA_OK after enqueueing; errors as listed above.
+ */
+bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, const void *v,
+                         const float *thresholds, int causal, void *out,
+                         const bsfa_skip_stats *skip_stats /* may be NULL */, void *hip_stream);
+
+/*
+ * Calibration of per-head thresholds (Section 4.2 reduced over query positions): runs the
+ * score / block-maximum half of the forward pass (Eq. 5-6) on a calibration batch and, for
+ * each query head and each target skip fraction f, returns the order statistic x_r,
+ * r = floor(f * n), of the n block maxima of that head's gateable tiles sorted ascending
+ * (-INFINITY if r == 0, +INFINITY if r == n).  With the keep rule s_max >= threshold exactly r
+ * tiles of the calibration batch are skipped, absent ties.
+ *   target_skip_fractions HOST [n_levels], each in [0, 1]
+ *   thresholds_out        HOST [n_levels][n_q_heads]
+ *   workspace             DEVICE, at least bsfa_calibrate_workspace_bytes(p) bytes
+ * p->thresholds_per_tile must be 0.  Synchronises hip_stream.
+ */
+bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, int causal,
+                           const float *target_skip_fractions, int n_levels,
+                           float *thresholds_out, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+
+/* Bytes of device workspace bsfa_calibrate needs for *p (0 if *p is invalid). */
+size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p);
+
+/* Tile shapes and head dims this build supports: fills up to `cap` entries of each array with
+ * (block_m, block_n, head_dim) triples and returns the number of supported triples. */
+int bsfa_query_build(int32_t *block_m, int32_t *block_n, int32_t *head_dim, int cap);
+
+const char *bsfa_status_string(bsfa_status s);
+const char *bsfa_last_error(void); /* thread-local, valid until the next failing call */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSFA_H */

@@ -1,0 +1,186 @@
+"""ctypes binding of libbsfa.so (see include/bsfa.h).  Argument marshalling only: every step of
+the attention path runs inside the library's HIP kernels.  PyTorch supplies device memory and
+the current stream; there is no fallback — if the library is missing or a call fails, this
+module raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbsfa.so")
+
+BSFA_OK = 0
+STATUS_NAMES = {0: "BSFA_OK", -1: "BSFA_ERR_NULL", -2: "BSFA_ERR_SHAPE", -3: "BSFA_ERR_DTYPE",
+                -4: "BSFA_ERR_UNSUPPORTED", -5: "BSFA_ERR_WORKSPACE", -6: "BSFA_ERR_HIP"}
+EXPORTS = ["bsfa_forward", "bsfa_calibrate", "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
+           "bsfa_status_string", "bsfa_last_error"]
+
+
+class BsfaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, str(status)), message))
+        self.status = status
+
+
+class bsfa_problem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("batch", "n_q_heads", "n_kv_heads", "seqlen", "head_dim", "block_m", "block_n")] + \
+               [(n, ctypes.c_int64) for n in
+                ("q_stride_b", "q_stride_n", "q_stride_h", "k_stride_b", "k_stride_n", "k_stride_h",
+                 "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
+               [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32)]
+
+
+class bsfa_skip_stats(ctypes.Structure):
+    _fields_ = [("counts", ctypes.c_void_p), ("skip_mask", ctypes.c_void_p), ("block_max", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Opens libbsfa.so (built in-tree by build.build_lib / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2512_07011_amd.build` "
+                "(there is no fallback path)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.bsfa_forward.restype = ctypes.c_int
+        L.bsfa_forward.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, vp, vp, ctypes.c_int, vp,
+                                   ctypes.POINTER(bsfa_skip_stats), vp]
+        L.bsfa_calibrate.restype = ctypes.c_int
+        L.bsfa_calibrate.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
+                                     ctypes.POINTER(ctypes.c_float), ctypes.c_int,
+                                     ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
+        L.bsfa_calibrate_workspace_bytes.restype = ctypes.c_size_t
+        L.bsfa_calibrate_workspace_bytes.argtypes = [ctypes.POINTER(bsfa_problem)]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.bsfa_query_build.restype = ctypes.c_int
+        L.bsfa_query_build.argtypes = [i32p, i32p, i32p, ctypes.c_int]
+        L.bsfa_status_string.restype = ctypes.c_char_p
+        L.bsfa_status_string.argtypes = [ctypes.c_int]
+        L.bsfa_last_error.restype = ctypes.c_char_p
+        L.bsfa_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != BSFA_OK:
+        raise BsfaError(status, lib().bsfa_last_error().decode())
+
+
+def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], out: Optional[torch.Tensor],
+                 block_m: int, block_n: int, thresholds_per_tile: bool = False) -> bsfa_problem:
+    """Descriptor for [B, N, H, d] views (any strides with a contiguous last dimension)."""
+    B, N, Hq, d = q.shape
+    p = bsfa_problem()
+    p.batch, p.seqlen, p.n_q_heads, p.n_kv_heads, p.head_dim = B, N, Hq, k.shape[2], d
+    p.block_m, p.block_n = block_m, block_n
+    for name, t in (("q", q), ("k", k), ("v", v if v is not None else k), ("o", out if out is not None else q)):
+        if t.stride(3) != 1:
+            raise ValueError("%s: head dimension must be contiguous" % name)
+        setattr(p, name + "_stride_b", t.stride(0))
+        setattr(p, name + "_stride_n", t.stride(1))
+        setattr(p, name + "_stride_h", t.stride(2))
+    p.dtype = 0
+    p.thresholds_per_tile = int(thresholds_per_tile)
+    return p
+
+
+@dataclass
+class SkipStats:
+    counts: Optional[torch.Tensor] = None      # [B, Hq, 3] int64: skipped, gateable, reachable
+    skip_mask: Optional[torch.Tensor] = None   # [B, Hq, M_Q, ceil(M_KV/32)] int32 bit mask
+    block_max: Optional[torch.Tensor] = None   # [B, Hq, M_Q, M_KV] fp32, NaN where not gateable
+
+
+def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_mask=False, block_max=False) -> SkipStats:
+    B, N, Hq, _ = q.shape
+    mq, mkv = N // block_m, N // block_n
+    s = SkipStats()
+    if counts:
+        s.counts = torch.empty(B, Hq, 3, dtype=torch.int64, device=q.device)
+    if skip_mask:
+        s.skip_mask = torch.empty(B, Hq, mq, (mkv + 31) // 32, dtype=torch.int32, device=q.device)
+    if block_max:
+        s.block_max = torch.empty(B, Hq, mq, mkv, dtype=torch.float32, device=q.device)
+    return s
+
+
+def _dev_check(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("bsfa: tensors must live on the GPU")
+
+
+def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: torch.Tensor,
+                 causal: bool = True, out: Optional[torch.Tensor] = None,
+                 skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """out = block-sparse attention of bf16 q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
+    GPU, [Hq] or [Hq, N/block_m].  Enqueues on ``stream`` (default: torch's current stream)."""
+    _dev_check(q, k, v, thresholds, out)
+    if not (q.dtype == k.dtype == v.dtype == torch.bfloat16):
+        raise TypeError("bsfa_forward: q, k, v must be bfloat16")
+    if thresholds.dtype != torch.float32 or not thresholds.is_contiguous():
+        raise TypeError("bsfa_forward: thresholds must be contiguous float32")
+    per_tile = thresholds.dim() == 2
+    B, N, Hq, d = q.shape
+    want = (Hq, N // block_m) if per_tile else (Hq,)
+    if tuple(thresholds.shape) != want:
+        raise ValueError("bsfa_forward: thresholds shape %s, expected %s" % (tuple(thresholds.shape), want))
+    if out is None:
+        out = torch.empty_like(q)
+    p = make_problem(q, k, v, out, block_m, block_n, per_tile)
+    st = None
+    if skip_stats is not None:
+        st = bsfa_skip_stats(
+            skip_stats.counts.data_ptr() if skip_stats.counts is not None else None,
+            skip_stats.skip_mask.data_ptr() if skip_stats.skip_mask is not None else None,
+            skip_stats.block_max.data_ptr() if skip_stats.block_max is not None else None)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    _check(lib().bsfa_forward(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), thresholds.data_ptr(),
+                              int(bool(causal)), out.data_ptr(), ctypes.byref(st) if st is not None else None,
+                              ctypes.c_void_p(s.cuda_stream)))
+    return out
+
+
+def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequence[float],
+                   causal: bool = True, block_m: int = 128, block_n: int = 64,
+                   workspace: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Per-head thresholds for each target skip fraction: CPU float32 tensor [n_levels, Hq]."""
+    _dev_check(q, k, workspace)
+    if not (q.dtype == k.dtype == torch.bfloat16):
+        raise TypeError("bsfa_calibrate: q, k must be bfloat16")
+    p = make_problem(q, k, None, None, block_m, block_n)
+    need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
+    if need == 0:
+        _check(lib().bsfa_calibrate(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), None, 0, None, None, 0, None))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    n = len(target_skip_fractions)
+    fr = (ctypes.c_float * n)(*[float(f) for f in target_skip_fractions])
+    outp = (ctypes.c_float * (n * q.shape[2]))()
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    _check(lib().bsfa_calibrate(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), fr, n, outp,
+                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                ctypes.c_void_p(s.cuda_stream)))
+    return torch.tensor(list(outp), dtype=torch.float32).view(n, q.shape[2])
+
+
+def bsfa_query_build():
+    """List of (block_m, block_n, head_dim) triples the library was built for."""
+    n = lib().bsfa_query_build(None, None, None, 0)
+    bm, bn, hd = ((ctypes.c_int32 * n)() for _ in range(3))
+    lib().bsfa_query_build(bm, bn, hd, n)
+    return [(bm[i], bn[i], hd[i]) for i in range(n)]

@@ -1,0 +1,203 @@
+// C ABI of libbsfa.so: argument validation, launch set-up, calibration driver, error strings.
+#include "../../include/bsfa.h"
+#include "bsfa_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+bsfa_status fail(bsfa_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bsfa_status check_problem(const bsfa_problem *p)
+{
+    if (!p) return fail(BSFA_ERR_NULL, "problem descriptor is NULL");
+    if (p->dtype != BSFA_BF16) return fail(BSFA_ERR_DTYPE, "dtype %d not supported (bf16 only)", p->dtype);
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->seqlen < 1 || p->head_dim < 1)
+        return fail(BSFA_ERR_SHAPE, "batch, head counts, seqlen and head_dim must be positive");
+    if (p->n_q_heads % p->n_kv_heads)
+        return fail(BSFA_ERR_SHAPE, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", p->n_q_heads, p->n_kv_heads);
+    if (p->block_m < 1 || p->block_n < 1)
+        return fail(BSFA_ERR_SHAPE, "block_m and block_n must be positive");
+    if (!bsfa::shape_supported(p->head_dim, p->block_m, p->block_n))
+        return fail(BSFA_ERR_UNSUPPORTED, "head_dim %d with tile %dx%d is not built (see bsfa_query_build)",
+                    p->head_dim, p->block_m, p->block_n);
+    if (p->seqlen % p->block_m || p->seqlen % p->block_n)
+        return fail(BSFA_ERR_SHAPE, "seqlen %d is not a multiple of block_m %d and block_n %d", p->seqlen,
+                    p->block_m, p->block_n);
+    const int64_t st[12] = {p->q_stride_b, p->q_stride_n, p->q_stride_h, p->k_stride_b, p->k_stride_n, p->k_stride_h,
+                            p->v_stride_b, p->v_stride_n, p->v_stride_h, p->o_stride_b, p->o_stride_n, p->o_stride_h};
+    for (int x = 0; x < 12; ++x) {
+        if (st[x] < 0 || st[x] % 8) return fail(BSFA_ERR_SHAPE, "stride #%d = %lld must be a non-negative multiple of 8 elements", x, (long long)st[x]);
+        if (x % 3 != 0 && st[x] < p->head_dim) return fail(BSFA_ERR_SHAPE, "token/head stride #%d = %lld is smaller than head_dim", x, (long long)st[x]);
+    }
+    if (p->thresholds_per_tile != 0 && p->thresholds_per_tile != 1)
+        return fail(BSFA_ERR_SHAPE, "thresholds_per_tile must be 0 or 1");
+    return BSFA_OK;
+}
+
+void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
+{
+    memset(&fp, 0, sizeof(fp));
+    fp.qsb = p->q_stride_b; fp.qsn = p->q_stride_n; fp.qsh = p->q_stride_h;
+    fp.ksb = p->k_stride_b; fp.ksn = p->k_stride_n; fp.ksh = p->k_stride_h;
+    fp.vsb = p->v_stride_b; fp.vsn = p->v_stride_n; fp.vsh = p->v_stride_h;
+    fp.osb = p->o_stride_b; fp.osn = p->o_stride_n; fp.osh = p->o_stride_h;
+    fp.batch = p->batch; fp.hq = p->n_q_heads; fp.hkv = p->n_kv_heads;
+    fp.group = p->n_q_heads / p->n_kv_heads;
+    fp.seqlen = p->seqlen;
+    fp.mq = p->seqlen / p->block_m;
+    fp.mkv = p->seqlen / p->block_n;
+    fp.mask_words = (fp.mkv + 31) / 32;
+    fp.causal = causal ? 1 : 0;
+    fp.tau_per_tile = p->thresholds_per_tile;
+    fp.scale = 1.0f / sqrtf((float)p->head_dim);
+    fp.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->head_dim));
+}
+
+}  // namespace
+
+extern "C" {
+
+bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, const void *v,
+                         const float *thresholds, int causal, void *out,
+                         const bsfa_skip_stats *skip_stats, void *hip_stream)
+{
+    bsfa_status s = check_problem(p);
+    if (s != BSFA_OK) return s;
+    if (!q || !k || !v || !thresholds || !out) return fail(BSFA_ERR_NULL, "q, k, v, thresholds and out must be non-NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+        return fail(BSFA_ERR_SHAPE, "q, k, v and out must be 16-byte aligned");
+    bsfa::FwdParams fp;
+    fill_params(fp, p, causal);
+    fp.q = static_cast<const uint16_t *>(q);
+    fp.k = static_cast<const uint16_t *>(k);
+    fp.v = static_cast<const uint16_t *>(v);
+    fp.out = static_cast<uint16_t *>(out);
+    fp.tau = thresholds;
+    if (skip_stats) {
+        fp.counts = reinterpret_cast<unsigned long long *>(skip_stats->counts);
+        fp.skip_mask = skip_stats->skip_mask;
+        fp.block_max = skip_stats->block_max;
+    }
+    hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, false, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
+    return BSFA_OK;
+}
+
+size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
+{
+    if (check_problem(p) != BSFA_OK) return 0;
+    const size_t mq = (size_t)(p->seqlen / p->block_m), mkv = (size_t)(p->seqlen / p->block_n);
+    return (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float) + 256;
+}
+
+bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, int causal,
+                           const float *target_skip_fractions, int n_levels, float *thresholds_out,
+                           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    bsfa_status s = check_problem(p);
+    if (s != BSFA_OK) return s;
+    if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate produces per-head thresholds only");
+    if (!q || !k || !target_skip_fractions || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, fractions and thresholds_out must be non-NULL");
+    if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
+    for (int l = 0; l < n_levels; ++l)
+        if (!(target_skip_fractions[l] >= 0.f && target_skip_fractions[l] <= 1.f))
+            return fail(BSFA_ERR_SHAPE, "target skip fraction #%d = %g is outside [0, 1]", l, (double)target_skip_fractions[l]);
+    if (!aligned16(q) || !aligned16(k)) return fail(BSFA_ERR_SHAPE, "q and k must be 16-byte aligned");
+    const size_t need = bsfa_calibrate_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need)
+        return fail(BSFA_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    bsfa::FwdParams fp;
+    fill_params(fp, p, causal);
+    fp.q = static_cast<const uint16_t *>(q);
+    fp.k = static_cast<const uint16_t *>(k);
+    fp.block_max = reinterpret_cast<float *>((reinterpret_cast<uintptr_t>(workspace) + 255) & ~(uintptr_t)255);
+    // the score half of the kernel reads a threshold per work item but never acts on it
+    fp.tau = fp.block_max;
+    fp.tau_per_tile = 0;
+    hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
+
+    // selection on the host: per head, order statistic of the gateable block maxima
+    const size_t mq = (size_t)fp.mq, mkv = (size_t)fp.mkv;
+    const size_t per_head = mq * mkv;
+    std::vector<float> host((size_t)p->batch * p->n_q_heads * per_head);
+    e = hipMemcpyAsync(host.data(), fp.block_max, host.size() * sizeof(float), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration copy failed: %s", hipGetErrorString(e));
+    std::vector<float> vals;
+    for (int h = 0; h < p->n_q_heads; ++h) {
+        vals.clear();
+        for (int b = 0; b < p->batch; ++b) {
+            const float *src = host.data() + ((size_t)b * p->n_q_heads + h) * per_head;
+            for (size_t x = 0; x < per_head; ++x)
+                if (!std::isnan(src[x])) vals.push_back(src[x]);
+        }
+        const size_t n = vals.size();
+        for (int l = 0; l < n_levels; ++l) {
+            const size_t r = (size_t)std::floor((double)target_skip_fractions[l] * (double)n);
+            float t;
+            if (r == 0) t = -INFINITY;
+            else if (r >= n) t = INFINITY;
+            else {
+                std::nth_element(vals.begin(), vals.begin() + r, vals.end());
+                t = vals[r];
+            }
+            thresholds_out[(size_t)l * p->n_q_heads + h] = t;
+        }
+    }
+    return BSFA_OK;
+}
+
+int bsfa_query_build(int32_t *block_m, int32_t *block_n, int32_t *head_dim, int cap)
+{
+    static const int bm[3] = {32, 64, 128};
+    static const int hd[2] = {64, 128};
+    int n = 0;
+    for (int d = 0; d < 2; ++d)
+        for (int m = 0; m < 3; ++m) {
+            if (n < cap) {
+                if (block_m) block_m[n] = bm[m];
+                if (block_n) block_n[n] = bsfa::kBlockN;
+                if (head_dim) head_dim[n] = hd[d];
+            }
+            ++n;
+        }
+    return n;
+}
+
+const char *bsfa_status_string(bsfa_status s)
+{
+    switch (s) {
+    case BSFA_OK: return "BSFA_OK";
+    case BSFA_ERR_NULL: return "BSFA_ERR_NULL";
+    case BSFA_ERR_SHAPE: return "BSFA_ERR_SHAPE";
+    case BSFA_ERR_DTYPE: return "BSFA_ERR_DTYPE";
+    case BSFA_ERR_UNSUPPORTED: return "BSFA_ERR_UNSUPPORTED";
+    case BSFA_ERR_WORKSPACE: return "BSFA_ERR_WORKSPACE";
+    case BSFA_ERR_HIP: return "BSFA_ERR_HIP";
+    }
+    return "BSFA_ERR_UNKNOWN";
+}
+
+const char *bsfa_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,34 @@
+// Internal declarations shared by the translation units of libbsfa.so (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bsfa {
+
+// Key/value block rows; the library is built for B_N = 64 only.
+constexpr int kBlockN = 64;
+
+struct FwdParams {
+    const uint16_t *q, *k, *v;       // bf16 bit patterns
+    uint16_t *out;
+    const float *tau;                // [hq] or [hq][mq]
+    int64_t qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;
+    int batch, hq, hkv, group, seqlen, mq, mkv;
+    int causal, tau_per_tile;
+    float scale;                     // 1/sqrt(d): natural score units, used by the gate
+    float scale_log2;                // log2(e)/sqrt(d): softmax evaluated with exp2
+    unsigned long long *counts;      // [batch][hq][3] or null
+    uint32_t *skip_mask;             // [batch][hq][mq][mask_words] or null
+    float *block_max;                // [batch][hq][mq][mkv] or null
+    int mask_words;
+};
+
+// Launches the forward kernel (calib == false) or its score/block-maximum half only
+// (calib == true: no V, no softmax, no output; block_max must be non-null).
+// Returns hipSuccess or the launch error; hipErrorInvalidValue for an unsupported
+// (head_dim, block_m) pair.
+hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool calib, hipStream_t stream);
+
+bool shape_supported(int head_dim, int block_m, int block_n);
+
+}  // namespace bsfa
