@@ -38,7 +38,7 @@ class ParityReport:
 
 
 def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None, block_max_gpu=None,
-            items=None) -> ParityReport:
+            items=None, oracle_result=None) -> ParityReport:
     """q, k, v: the bf16 tensors the kernel saw (any device); tau numpy/torch [Hq] or [Hq, M_Q];
     out_gpu [B,N,Hq,d]; skip_mask_gpu [B,Hq,M_Q,W]; block_max_gpu [B,Hq,M_Q,M_KV]."""
     qf, kf, vf = (t.detach().float().cpu() for t in (q, k, v))
@@ -48,7 +48,7 @@ def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None,
     if items is None:
         items = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(mq)]
     items = np.asarray(items, dtype=np.int32).reshape(-1, 3)
-    r = orc.forward_items(qf, kf, vf, tau, block_m, block_n, causal, items)
+    r = oracle_result if oracle_result is not None else orc.forward_items(qf, kf, vf, tau, block_m, block_n, causal, items)
     ib, ih, ii = items[:, 0], items[:, 1], items[:, 2]
 
     tau_item = tau[ih, ii] if tau.ndim == 2 else tau[ih]
