@@ -1,16 +1,25 @@
 // Block-Sparse FlashAttention forward kernel for gfx950 (MI355X), wave64, bf16 MFMA.
 //
-// One workgroup = one query tile Q_i (B_M = 32 * NW rows, NW waves, 32 query rows per wave) of
-// one head; it walks the reachable key blocks j in ascending order (Algorithm 1 of the paper):
+// One workgroup = one query tile Q_i (B_M = 32 * QB * NW rows: NW waves, QB 32-row column blocks
+// per wave) of one head; it walks the reachable key blocks j in ascending order (Algorithm 1):
 //   S_ij^T = K_j Q_i^T        32x32x16 bf16 MFMA, fp32 accumulate                 (Eq. 5)
 //   s_max  = max S_ij         lane max -> wave max -> cross-wave max through LDS   (Eq. 6)
 //   gate   : s_max / sqrt(d) >= T keeps the block; blocks touching the causal boundary bypass
-//            the gate (Section 4.1).  The branch is workgroup-uniform.
-//   kept   : V_j is fetched only now, exp2-based online softmax, O^T += V_j^T P^T.
+//            the gate (Section 4.1).  The decision is workgroup-uniform.
+//   kept   : V_j is requested only after the decision, exp2-based online softmax,
+//            O^T += V_j^T P^T.
 // The transposed products keep everything of one query row inside one lane pair (l, l^32):
 // the S^T accumulator layout (column = query) is already the B-operand layout of the second
 // MFMA up to a permutation of the keys, and the same permutation is applied to V when its
 // A operand is gathered from LDS with the transposing read, so P never leaves registers.
+//
+// Software pipeline (one barrier per key block).  While block j is being finished the scores
+// of block j+1 are already computed, so its gate decision is known one block ahead:
+//   iteration j:  S_{j+1} = K_{j+1} Q^T  (MFMA)   overlapped with   softmax(S_j)  (VALU)
+//                 block max of S_{j+1} -> LDS;  wait for own global->LDS copies;  barrier
+//                 decide keep_{j+1};  request V_{j+1} (only if kept) and K_{j+3}
+//                 O^T += V_j^T P_j^T   (MFMA, V_j landed before the barrier)
+// K and V tiles go HBM -> LDS directly (no register staging), two buffers each.
 #include "bsfa_internal.h"
 
 #include <math.h>
@@ -18,16 +27,19 @@
 namespace bsfa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+#define GLB_PTR(T, p) ((const __attribute__((address_space(1))) T *)(p))
 
 // ---- LDS tile layout --------------------------------------------------------------------
-// A K or V tile is 64 rows x D bf16.  It is stored as 16-byte chunks, row-major, with the
-// chunk index XOR-ed by a function of the row so that the operand gathers below spread over
-// the banks.  Any per-row bijection is correct; these two are chosen for the two read shapes.
+// A K or V tile is 64 rows x D bf16, stored as 16-byte chunks, row-major, the chunk index
+// XOR-ed with a function of the row so that the operand gathers spread over the banks.  The
+// swizzle is applied on the global side of the copy (lane -> which chunk it fetches); the LDS
+// side of a direct copy is always linear (wave base + lane * 16 bytes).
 template <int D> __device__ __forceinline__ int swz_k(int row)
 {
     return (D == 128) ? (row & 15) : ((row >> 1) & 7);
@@ -37,34 +49,56 @@ template <int D> __device__ __forceinline__ int swz_v(int row)
     return (D == 128) ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
 }
 
-// Global -> registers: thread tid fetches chunks sigma = r * NT + tid of the linear LDS image,
-// i.e. the logical chunk that the swizzle places there.
+// Element offset (relative to the tile's first row) of the chunk thread `tid` copies in
+// repetition r.
 template <int D, int NT, bool ISV>
-__device__ __forceinline__ void tile_fetch(uint4 (&st)[64 * (D / 8) / NT], const uint16_t *base,
-                                           int64_t stride_n, int tid)
+__device__ __forceinline__ int chunk_src_offset(int r, int tid, int stride_n)
 {
     constexpr int CPR = D / 8;
-#pragma unroll
-    for (int r = 0; r < 64 * CPR / NT; ++r) {
-        int sigma = r * NT + tid;
-        int row = sigma / CPR, cp = sigma % CPR;
-        int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
-        st[r] = *reinterpret_cast<const uint4 *>(base + (int64_t)row * stride_n + 8 * c);
-    }
+    const int sigma = r * NT + tid;
+    const int row = sigma / CPR, cp = sigma % CPR;
+    const int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
+    return row * stride_n + 8 * c;
 }
+
+// Asynchronous HBM -> LDS copy of one 64 x D tile (completion is tracked by vmcnt).
 template <int D, int NT>
-__device__ __forceinline__ void tile_commit(const uint4 (&st)[64 * (D / 8) / NT], uint16_t *lds, int tid)
+__device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const int (&off)[64 * (D / 8) / NT],
+                                                uint16_t *lds_tile, int wave)
 {
 #pragma unroll
     for (int r = 0; r < 64 * (D / 8) / NT; ++r)
-        *reinterpret_cast<uint4 *>(lds + (size_t)(r * NT + tid) * 8) = st[r];
+        __builtin_amdgcn_global_load_lds(GLB_PTR(void, gtile + off[r]),
+                                         LDS_PTR(void, lds_tile + (r * NT + wave * 64) * 8), 16, 0, 0);
 }
 
-__device__ __forceinline__ float wave_max(float x)
+template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
+    const int x = __builtin_bit_cast(int, v);
+    return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, 0xf, 0xf, false)));
+}
+
+// max over lanes l and l^32, result in both lanes.  v_permlane32_swap exchanges the upper half
+// of its first operand with the lower half of its second: with two copies of x the first
+// register ends up holding x[l & 31] and the second x[32 + (l & 31)] in every lane.  Written as
+// one asm block so that the two copies are guaranteed to live in different registers.
+__device__ __forceinline__ float pair_max(float x)
+{
+    float a = x, b;
+    asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "=&v"(b));
+    return fmaxf(a, b);
+}
+
+// max over the wave of a value that is already equal in lanes l and l^32 (wave-uniform result)
+__device__ __forceinline__ float wave_max_paired(float x)
+{
+    x = dpp_max<0xB1>(x);     // quad_perm [1,0,3,2]
+    x = dpp_max<0x4E>(x);     // quad_perm [2,3,0,1]
+    x = dpp_max<0x141>(x);    // row_half_mirror
+    x = dpp_max<0x140>(x);    // row_mirror
+    const int xi = __builtin_bit_cast(int, x);
+    return fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)),
+                 __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)));
 }
 
 // Work decomposition.  With at least 8 (batch, KV head) pairs the pair is chosen by the low
@@ -94,24 +128,31 @@ __device__ __forceinline__ bool decode_work(const FwdParams &p, int w, int &b, i
     return true;
 }
 
-template <int D, int NW, bool CALIB>
-__global__ void __launch_bounds__(NW * 64) bsfa_fwd_kernel(const FwdParams p)
+template <int QB> struct ScoreTile {
+    f32x16 s[2][QB];      // S^T: [32-key half][32-query column block], raw q.k (no 1/sqrt(d))
+    float mx[QB];         // row max of the lane's query, equal in lanes l and l^32
+    bool keep;            // workgroup-uniform gate decision
+};
+
+template <int D, int NW, int QB, bool CALIB>
+__global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
 {
     constexpr int NT = NW * 64;
-    constexpr int BM = NW * 32;
+    constexpr int BM = NW * QB * 32;
     constexpr int BN = kBlockN;
     constexpr int KS = D / 16;       // MFMA k-steps over the head dim
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int CPR = D / 8;       // 16-byte chunks per tile row
     constexpr int NST = 64 * CPR / NT;
 
-    __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][BN * D];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_v[CALIB ? 8 : BN * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t lds_k[2][BN * D];
+    __shared__ __attribute__((aligned(1024))) uint16_t lds_v[CALIB ? 1 : 2][CALIB ? 8 : BN * D];
     __shared__ float lds_red[2][NW];
 
     int b, h, i;
     if (!decode_work(p, blockIdx.x, b, h, i)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hh = lane >> 5;
     const int g = h / p.group;
 
@@ -126,86 +167,105 @@ __global__ void __launch_bounds__(NW * 64) bsfa_fwd_kernel(const FwdParams p)
     const uint16_t *vbase = p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
     const float tau = p.tau[p.tau_per_tile ? (int64_t)h * p.mq + i : h];
 
-    // Q_i^T as the B operand: lane holds query (wave*32 + l32), head-dim slice 16s + 8hh .. +7
-    bf16x8 qreg[KS];
-    {
-        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (row0 + wave * 32 + l32) * p.qsn + (int64_t)h * p.qsh + 8 * hh;
+    int koff[NST], voff[NST];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+    for (int r = 0; r < NST; ++r) {
+        koff[r] = chunk_src_offset<D, NT, false>(r, tid, (int)p.ksn);
+        voff[r] = chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
+    }
+    const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
+
+    // Q_i^T as the B operand: lane holds query (wave*32*QB + 32*qb + l32), head-dim slice 16s + 8hh .. +7
+    bf16x8 qreg[QB][KS];
+    int q_row[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        q_row[qb] = (int)row0 + (wave * QB + qb) * 32 + l32;
+        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)q_row[qb] * p.qsn + (int64_t)h * p.qsh + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     }
 
-    f32x16 oacc[DB];
+    f32x16 oacc[DB][QB];
 #pragma unroll
     for (int x = 0; x < DB; ++x)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[x][e] = 0.f;
-    float m_run = -INFINITY;   // running row max, log2 units (score * log2(e)/sqrt(d))
-    float l_run = 0.f;         // this lane's share of the running normaliser
-    const int q_row = (int)(row0) + wave * 32 + l32;      // token index of this lane's query
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[x][qb][e] = 0.f;
+    float m_run[QB], l_run[QB];    // running row max (log2 units) and this lane's share of the normaliser
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+    }
 
     unsigned long long n_skipped = 0;
     uint32_t mask_word = 0;
     const int64_t stat_row = ((int64_t)b * p.hq + h) * p.mq + i;
 
-    uint4 stage[NST];
-    tile_fetch<D, NT, false>(stage, kbase, p.ksn, tid);
-    tile_commit<D, NT>(stage, lds_k[0], tid);
-    __syncthreads();
+    auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
-    for (int j = 0; j < n_blk; ++j) {
-        const uint16_t *kcur = lds_k[j & 1];
-        const bool more = (j + 1 < n_blk);
-        if (more) tile_fetch<D, NT, false>(stage, kbase + (int64_t)(j + 1) * BN * p.ksn, p.ksn, tid);
-
-        // ---- S^T = K_j Q_i^T : two 32-key halves, raw (unscaled) scores --------------------
-        f32x16 sacc[2];
+    // S^T of block j from the K tile in `kt`, causal mask on boundary blocks, row maxima, and the
+    // wave's block maximum into lds_red[j & 1]
+    auto compute_scores = [&](ScoreTile<QB> &t, const uint16_t *kt, int j) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) t.s[kb][qb][e] = 0.f;
             const int row = 32 * kb + l32;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int c = (2 * s + hh) ^ swz_k<D>(row);
-                bf16x8 a = *reinterpret_cast<const bf16x8 *>(kcur + (row * CPR + c) * 8);
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], sacc[kb], 0, 0, 0);
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kt + (row * CPR + c) * 8);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    t.s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], t.s[kb][qb], 0, 0, 0);
             }
         }
-
-        const bool gated = p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi);
+        const bool gated = is_gated(j);
         if (p.causal && !gated) {
-            // boundary block: key token > query token is masked out
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (key > q_row) sacc[kb][e] = -INFINITY;
-                }
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
+                        if (key > q_row[qb]) t.s[kb][qb][e] = -INFINITY;
+                    }
         }
-        float mx = -INFINITY;
+        float all = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int qb = 0; qb < QB; ++qb) {
+            float mx = -INFINITY;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));              // row max of this lane pair's query
-
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t.s[kb][qb][e]);
+            t.mx[qb] = pair_max(mx);
+            all = fmaxf(all, t.mx[qb]);
+        }
         if (gated) {
-            const float wm = wave_max(mx);
+            const float wm = wave_max_paired(all);
             if (lane == 0) lds_red[j & 1][wave] = wm;
         }
-        if (more) tile_commit<D, NT>(stage, lds_k[(j + 1) & 1], tid);
-        __syncthreads();
+    };
 
+    // gate decision for block j (after the barrier that publishes lds_red[j & 1]) + statistics
+    auto decide = [&](ScoreTile<QB> &t, int j) {
         bool keep = true;
         float bmax = NAN;
-        if (gated) {
+        if (is_gated(j)) {
             float r = lds_red[j & 1][0];
 #pragma unroll
             for (int w = 1; w < NW; ++w) r = fmaxf(r, lds_red[j & 1][w]);
             bmax = r * p.scale;                          // natural score units (Eq. 5-6)
             keep = (bmax >= tau);                        // skip iff s_max < T
         }
+        t.keep = keep;
         if (tid == 0) {
             if (p.block_max) p.block_max[stat_row * p.mkv + j] = bmax;
             if (!keep) {
@@ -217,58 +277,102 @@ __global__ void __launch_bounds__(NW * 64) bsfa_fwd_kernel(const FwdParams p)
                 mask_word = 0;
             }
         }
-        if (CALIB || !keep) continue;
+    };
 
-        // ---- kept block: fetch V_j now, online softmax, O^T += V_j^T P^T --------------------
-        if constexpr (!CALIB) {
-            uint4 vst[NST];
-            tile_fetch<D, NT, true>(vst, vbase + (int64_t)j * BN * p.vsn, p.vsn, tid);
-
-            const float m_new = fmaxf(m_run, mx * p.scale_log2);
+    // online-softmax update of the running statistics with block `t`; P (bf16) into pb
+    auto softmax = [&](ScoreTile<QB> &t, bf16x8 (&pb)[4][QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float m_new = fmaxf(m_run[qb], t.mx[qb] * p.scale_log2);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            m_run = m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+            m_run[qb] = m_new;
             float psum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], p.scale_log2, -m_use));
-                    sacc[kb][e] = pe;
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(t.s[kb][qb][e], p.scale_log2, -m_use));
+                    t.s[kb][qb][e] = pe;
                     psum += pe;
                 }
-            l_run = l_run * alpha + psum;
+            l_run[qb] = l_run[qb] * alpha + psum;
             if (__any(alpha != 1.0f)) {
 #pragma unroll
                 for (int x = 0; x < DB; ++x)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[x][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) oacc[x][qb][e] *= alpha;
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pb[u][qb][e] = (__bf16)t.s[u >> 1][qb][8 * (u & 1) + e];
+        }
+    };
 
-            tile_commit<D, NT>(vst, lds_v, tid);
-            __syncthreads();
-
-            const int L = lane & 15, g16 = (lane >> 4) & 1;
+    // O^T += V^T P^T for the V tile in `vt`
+    auto pv = [&](const bf16x8 (&pb)[4][QB], const uint16_t *vt) {
+        const int L = lane & 15, g16 = (lane >> 4) & 1;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {                 // 16 keys per MFMA k-step
-                bf16x8 pb;
+        for (int u = 0; u < 4; ++u) {                     // 16 keys per MFMA k-step
+            const int r0 = 16 * u + 4 * hh + (L >> 2);
+            const int r1 = r0 + 8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[u >> 1][8 * (u & 1) + e];
-                const int r0 = 16 * u + 4 * hh + (L >> 2);
-                const int r1 = r0 + 8;
+            for (int x = 0; x < DB; ++x) {
+                const int dcol = 32 * x + 16 * g16 + 4 * (L & 3);         // element column
+                const int c = dcol >> 3, half = (dcol >> 2) & 1;
+                const uint16_t *a0 = vt + (r0 * CPR + (c ^ swz_v<D>(r0))) * 8 + 4 * half;
+                const uint16_t *a1 = vt + (r1 * CPR + (c ^ swz_v<D>(r1))) * 8 + 4 * half;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a1));
+                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-                for (int x = 0; x < DB; ++x) {
-                    const int dcol = 32 * x + 16 * g16 + 4 * (L & 3);     // element column
-                    const int c = dcol >> 3, half = (dcol >> 2) & 1;
-                    const uint16_t *a0 = lds_v + (r0 * CPR + (c ^ swz_v<D>(r0))) * 8 + 4 * half;
-                    const uint16_t *a1 = lds_v + (r1 * CPR + (c ^ swz_v<D>(r1))) * 8 + 4 * half;
-                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
-                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a1));
-                    s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[x], 0, 0, 0);
-                }
+                for (int qb = 0; qb < QB; ++qb)
+                    oacc[x][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[u][qb], oacc[x][qb], 0, 0, 0);
             }
         }
+    };
+
+    auto wait_copies_and_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0): this wave's HBM -> LDS copies have landed
+        __syncthreads();
+    };
+
+    // one pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`)
+    auto stage = [&](ScoreTile<QB> &cur, ScoreTile<QB> &nxt, int j) {
+        const bool has_next = (j + 1 < n_blk);
+        bf16x8 pb[4][QB];
+        if (!CALIB && cur.keep) {
+            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1);
+            softmax(cur, pb);
+        } else {
+            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1);
+        }
+        wait_copies_and_barrier();
+        if (has_next) {
+            decide(nxt, j + 1);
+            if (!CALIB && nxt.keep) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v[CALIB ? 0 : ((j + 1) & 1)], wave);
+            if (j + 3 < n_blk) tile_copy_async<D, NT>(kbase + (int64_t)(j + 3) * kstep, koff, lds_k[(j + 1) & 1], wave);
+        }
+        if constexpr (!CALIB) {
+            if (cur.keep) pv(pb, lds_v[j & 1]);
+        }
+    };
+
+    // ---- prologue: K_0, K_1 in flight, scores and decision of block 0 -------------------------
+    ScoreTile<QB> ta, tb;
+    tile_copy_async<D, NT>(kbase, koff, lds_k[0], wave);
+    if (1 < n_blk) tile_copy_async<D, NT>(kbase + kstep, koff, lds_k[1], wave);
+    wait_copies_and_barrier();
+    compute_scores(ta, lds_k[0], 0);
+    wait_copies_and_barrier();
+    decide(ta, 0);
+    if (!CALIB && ta.keep) tile_copy_async<D, NT>(vbase, voff, lds_v[0], wave);
+    if (2 < n_blk) tile_copy_async<D, NT>(kbase + 2 * kstep, koff, lds_k[0], wave);
+
+    for (int j = 0; j < n_blk; j += 2) {
+        stage(ta, tb, j);
+        if (j + 1 < n_blk) stage(tb, ta, j + 1);
     }
 
     // ---- statistics ------------------------------------------------------------------------
@@ -283,24 +387,25 @@ __global__ void __launch_bounds__(NW * 64) bsfa_fwd_kernel(const FwdParams p)
         atomicAdd(c + 1, (unsigned long long)gateable);
         atomicAdd(c + 2, (unsigned long long)n_blk);
     }
-    if constexpr (CALIB) return;
 
     // ---- O_i = O~_i / l_i, written as bf16 ----------------------------------------------------
     if constexpr (!CALIB) {
-        const float l_tot = l_run + __shfl_xor(l_run, 32);
-        const float inv = 1.0f / l_tot;
-        uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row * p.osn + (int64_t)h * p.osh;
 #pragma unroll
-        for (int x = 0; x < DB; ++x)
+        for (int qb = 0; qb < QB; ++qb) {
+            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+            const float inv = 1.0f / l_tot;
+            uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row[qb] * p.osn + (int64_t)h * p.osh;
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const int d0 = 32 * x + 8 * e4 + 4 * hh;
-                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                bf16x4 o;
+            for (int x = 0; x < DB; ++x)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][4 * e4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + d0) = o;
-            }
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int d0 = 32 * x + 8 * e4 + 4 * hh;
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][qb][4 * e4 + e] * inv);
+                    *reinterpret_cast<bf16x4 *>(op + d0) = o;
+                }
+        }
     }
 }
 
@@ -310,7 +415,7 @@ __global__ void zero_counts_kernel(unsigned long long *c, int n)
     if (t < n) c[t] = 0ull;
 }
 
-template <int D, int NW>
+template <int D, int NW, int QB>
 static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
 {
     const int pairs = p.batch * p.hkv;
@@ -321,9 +426,9 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, true>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, true>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, false>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, false>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -337,10 +442,12 @@ bool shape_supported(int head_dim, int block_m, int block_n)
 hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool calib, hipStream_t stream)
 {
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
-#define BSFA_CASE(DD, NN) \
-    if (head_dim == DD && block_m == 32 * NN) return launch_t<DD, NN>(p, calib, stream);
-    BSFA_CASE(64, 1) BSFA_CASE(64, 2) BSFA_CASE(64, 4)
-    BSFA_CASE(128, 1) BSFA_CASE(128, 2) BSFA_CASE(128, 4)
+    // the copies address a tile with 32-bit element offsets
+    if (p.ksn * 64 > 0x7fffffffLL || p.vsn * 64 > 0x7fffffffLL) return hipErrorInvalidValue;
+#define BSFA_CASE(DD, NN, QQ) \
+    if (head_dim == DD && block_m == 32 * NN * QQ) return launch_t<DD, NN, QQ>(p, calib, stream);
+    BSFA_CASE(64, 1, 1) BSFA_CASE(64, 2, 1) BSFA_CASE(64, 4, 1)
+    BSFA_CASE(128, 1, 1) BSFA_CASE(128, 2, 1) BSFA_CASE(128, 4, 1)
 #undef BSFA_CASE
     return hipErrorInvalidValue;
 }
