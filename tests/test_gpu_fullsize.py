@@ -1,0 +1,118 @@
+"""Full-size checks in the launch configuration bench.py times (Llama-3.1-8B-shaped layer,
+128x64 tiles, 32K-128K tokens): oracle parity on sampled (head, query tile) items, and
+properties that hold at any size and need no oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_07011_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def gen(n, seed):
+    shp = synth.llama_shape(n)
+    return shp, synth.llama_layer(seed, shp, device=DEV)
+
+
+@pytest.mark.parametrize("n", [32768, 65536, 131072])
+def test_sampled_parity_at_half_skip(n):
+    shp, (qc, kc, _) = gen(n, 1)
+    tau = binding.bsfa_calibrate(qc, kc, [0.5])[0]
+    del qc, kc
+    shp, (q, k, v) = gen(n, 0)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=st)
+    torch.cuda.synchronize()
+    c = st.counts.cpu().numpy()[0]
+    assert abs(c[:, 0].sum() / c[:, 1].sum() - 0.5) < 0.05           # held-out seed tracks the target
+    assert (c[:, 2] == shp.m_q * (shp.m_q + 1)).all() and (c[:, 1] == shp.m_q * (shp.m_q - 1)).all()
+    items = parity.sample_items(shp, n_random=1, seed=n)
+    rep = parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask, None, items=items)
+    print("N=%d: %d items, max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips"
+          % (n, rep.n_items, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
+    assert rep.skipped > 0
+
+
+def test_sparsity_sweep_128k():
+    """Skip targets 25/75/90 % at 128K (0 and 50 % are covered above and by the dense tests)."""
+    shp, (qc, kc, _) = gen(131072, 1)
+    fr = [0.25, 0.75, 0.9]
+    taus = binding.bsfa_calibrate(qc, kc, fr)
+    del qc, kc
+    shp, (q, k, v) = gen(131072, 0)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    items = parity.sample_items(shp, n_random=0, seed=5)[::2]
+    for f, tau in zip(fr, taus):
+        out = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=st)
+        torch.cuda.synchronize()
+        c = st.counts.cpu().numpy()[0]
+        assert abs(c[:, 0].sum() / c[:, 1].sum() - f) < 0.05
+        rep = parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask, None, items=items)
+        print("f=%.2f: max_abs %.3g mean_abs %.3g flips %d" % (f, rep.max_abs, rep.mean_abs, rep.mask_mismatch))
+
+
+def test_constant_v_128k():
+    """All V rows equal v0: whatever is skipped, every output row is v0 (the skipped blocks are
+    renormalised out, not zero-filled)."""
+    shp, (q, k, v) = gen(131072, 3)
+    tau = binding.bsfa_calibrate(q, k, [0.6])[0]
+    v0 = torch.linspace(-2, 2, 128, device=DEV).to(torch.bfloat16)
+    v[:] = v0
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV))
+    torch.cuda.synchronize()
+    err = (out.float() - v0.float()).abs().amax()
+    assert err <= 2.0 ** -6, float(err)             # one bf16 ulp at |v| <= 2 after fp32 accumulation
+
+
+def test_indicator_v_32k():
+    """V[t, c] = 1 iff (t // 64) % 128 == c: output column c is the softmax mass on key blocks
+    congruent to c, so it must be exactly 0 where all of them were skipped, and rows sum to 1."""
+    shp, (q, k, v) = gen(32768, 4)
+    tau = binding.bsfa_calibrate(q, k, [0.7])[0]
+    blk = torch.arange(32768, device=DEV) // 64
+    v.zero_()
+    v[0, torch.arange(32768, device=DEV), :, blk % 128] = 1.0
+    st = binding.alloc_stats(q, 128, 64, counts=False, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=st)
+    torch.cuda.synchronize()
+    o = out.float().view(shp.m_q, 128, 32, 128)                               # [i, row, h, c]
+    assert (o.sum(-1) - 1).abs().max() < 2e-2
+    skipped = torch.from_numpy(parity.unpack_mask(st.skip_mask.cpu().numpy(), shp.m_kv)[0]).to(DEV)   # [h, i, j]
+    reach = (torch.arange(shp.m_kv, device=DEV)[None, :] * 64) <= (torch.arange(shp.m_q, device=DEV)[:, None] * 128 + 127)
+    kept = (~skipped) & reach[None]                                            # [h, i, j]
+    kept_col = kept.view(32, shp.m_q, shp.m_kv // 128, 128).any(dim=2)         # [h, i, c]
+    dead = ~kept_col.permute(1, 0, 2)                                          # [i, h, c]
+    assert dead.any()
+    assert (o.permute(0, 2, 3, 1)[dead] == 0).all()
+    # and mass arrives on every column whose only kept block is a boundary block
+    assert (o.permute(0, 2, 3, 1)[~dead].amax(dim=-1) > 0).all()
+
+
+def test_nan_poisoned_skipped_v_32k():
+    """Key blocks whose K rows are zero score 0 against every query, so with tau = 0.5 they are
+    skipped wherever the gate applies.  Their V rows are NaN: only the query tiles that overlap
+    them (where they bypass the gate) may see it; every other row must equal the clean run."""
+    shp, (q, k, v) = gen(32768, 6)
+    poisoned = [3, 70, 201, 444]
+    tau = torch.full((32,), 0.5, device=DEV)
+    for j in poisoned:
+        k[0, j * 64:(j + 1) * 64] = 0
+    clean = binding.bsfa_forward(q, k, v, tau).clone()
+    for j in poisoned:
+        v[0, j * 64:(j + 1) * 64] = float("nan")
+    st = binding.alloc_stats(q, 128, 64, counts=False, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau, skip_stats=st)
+    torch.cuda.synchronize()
+    m = parity.unpack_mask(st.skip_mask.cpu().numpy(), shp.m_kv)[0]           # [h, i, j]
+    for j in poisoned:
+        assert m[:, j // 2 + 1:, j].all()                                      # skipped wherever gateable
+    rows_ok = torch.ones(32768, dtype=torch.bool, device=DEV)
+    for j in poisoned:
+        i = j // 2
+        rows_ok[i * 128:(i + 1) * 128] = False
+    assert torch.isfinite(out[0, rows_ok].float()).all()
+    assert torch.equal(out[0, rows_ok], clean[0, rows_ok])
+    assert torch.isnan(out[0, ~rows_ok].float()).any()
