@@ -23,6 +23,9 @@
 #include "bsfa_internal.h"
 
 #include <math.h>
+#include <stdlib.h>
+
+#include <type_traits>
 
 namespace bsfa {
 
@@ -134,8 +137,8 @@ template <int QB> struct ScoreTile {
     bool keep;            // workgroup-uniform gate decision
 };
 
-template <int D, int NW, int QB, bool CALIB>
-__global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
+template <int D, int NW, int QB, bool CALIB, int OCC>
+__global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams p)
 {
     constexpr int NT = NW * 64;
     constexpr int BM = NW * QB * 32;
@@ -200,24 +203,29 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
         l_run[qb] = 0.f;
     }
 
-    unsigned long long n_skipped = 0;
+    unsigned n_skipped = 0;      // workgroup-uniform statistics
     uint32_t mask_word = 0;
     const int64_t stat_row = ((int64_t)b * p.hq + h) * p.mq + i;
 
     auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
-    // S^T of block j from the K tile in `kt`, causal mask on boundary blocks, row maxima, and the
-    // wave's block maximum into lds_red[j & 1]
-    auto compute_scores = [&](ScoreTile<QB> &t, const uint16_t *kt, int j) {
+    // S^T of block j from the K tile in `kt`, row maxima, and the wave's block maximum into
+    // lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask, always reduced),
+    // which keeps the whole function free of branches.
+    auto compute_scores = [&](ScoreTile<QB> &t, const uint16_t *kt, int j, auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) t.s[kb][qb][e] = 0.f;
-            const int row = 32 * kb + l32;
+        }
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int row = 32 * kb + l32;
                 const int c = (2 * s + hh) ^ swz_k<D>(row);
                 const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kt + (row * CPR + c) * 8);
 #pragma unroll
@@ -225,17 +233,19 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
                     t.s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], t.s[kb][qb], 0, 0, 0);
             }
         }
-        const bool gated = is_gated(j);
-        if (p.causal && !gated) {
+        const bool gated = FAST ? true : is_gated(j);
+        if constexpr (!FAST) {
+            if (p.causal && !gated) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                        if (key > q_row[qb]) t.s[kb][qb][e] = -INFINITY;
-                    }
+                        for (int e = 0; e < 16; ++e) {
+                            const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
+                            if (key > q_row[qb]) t.s[kb][qb][e] = -INFINITY;
+                        }
+            }
         }
         float all = -INFINITY;
 #pragma unroll
@@ -255,10 +265,11 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
     };
 
     // gate decision for block j (after the barrier that publishes lds_red[j & 1]) + statistics
-    auto decide = [&](ScoreTile<QB> &t, int j) {
+    auto decide = [&](ScoreTile<QB> &t, int j, auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
         bool keep = true;
         float bmax = NAN;
-        if (is_gated(j)) {
+        if (FAST || is_gated(j)) {
             float r = lds_red[j & 1][0];
 #pragma unroll
             for (int w = 1; w < NW; ++w) r = fmaxf(r, lds_red[j & 1][w]);
@@ -266,26 +277,23 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
             keep = (bmax >= tau);                        // skip iff s_max < T
         }
         t.keep = keep;
-        if (tid == 0) {
-            if (p.block_max) p.block_max[stat_row * p.mkv + j] = bmax;
-            if (!keep) {
-                ++n_skipped;
-                mask_word |= 1u << (j & 31);
-            }
-            if (p.skip_mask && ((j & 31) == 31 || j == n_blk - 1)) {
-                p.skip_mask[stat_row * p.mask_words + (j >> 5)] = mask_word;
-                mask_word = 0;
-            }
+        n_skipped += keep ? 0 : 1;
+        mask_word |= (keep ? 0u : 1u) << (j & 31);
+        if (p.block_max && tid == 0) p.block_max[stat_row * p.mkv + j] = bmax;
+        if ((j & 31) == 31 || j == n_blk - 1) {
+            if (p.skip_mask && tid == 0) p.skip_mask[stat_row * p.mask_words + (j >> 5)] = mask_word;
+            mask_word = 0;
         }
     };
 
-    // online-softmax update of the running statistics with block `t`; P (bf16) into pb
-    auto softmax = [&](ScoreTile<QB> &t, bf16x8 (&pb)[4][QB]) {
+    // online-softmax update of the running statistics with block `t`; P (bf16) into pb; returns
+    // in alpha[] the factor the accumulator still has to be multiplied with
+    auto softmax = [&](ScoreTile<QB> &t, bf16x8 (&pb)[4][QB], float (&alpha)[QB]) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float m_new = fmaxf(m_run[qb], t.mx[qb] * p.scale_log2);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+            alpha[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
             m_run[qb] = m_new;
             float psum = 0.f;
 #pragma unroll
@@ -296,17 +304,23 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
                     t.s[kb][qb][e] = pe;
                     psum += pe;
                 }
-            l_run[qb] = l_run[qb] * alpha + psum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int x = 0; x < DB; ++x)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[x][qb][e] *= alpha;
-            }
+            l_run[qb] = l_run[qb] * alpha[qb] + psum;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pb[u][qb][e] = (__bf16)t.s[u >> 1][qb][8 * (u & 1) + e];
+        }
+    };
+
+    auto rescale = [&](const float (&alpha)[QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            if (__any(alpha[qb] != 1.0f)) {
+#pragma unroll
+                for (int x = 0; x < DB; ++x)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[x][qb][e] *= alpha[qb];
+            }
         }
     };
 
@@ -338,19 +352,23 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
         __syncthreads();
     };
 
-    // one pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`)
-    auto stage = [&](ScoreTile<QB> &cur, ScoreTile<QB> &nxt, int j) {
-        const bool has_next = (j + 1 < n_blk);
+    // One pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`).
+    // FAST: block j+1 exists and is gateable, so the look-ahead has no mask and no conditionals.
+    auto stage = [&](ScoreTile<QB> &cur, ScoreTile<QB> &nxt, int j, auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        const bool has_next = FAST || (j + 1 < n_blk);
         bf16x8 pb[4][QB];
+        float alpha[QB];
         if (!CALIB && cur.keep) {
-            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1);
-            softmax(cur, pb);
+            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1, fast_tag);
+            softmax(cur, pb, alpha);
+            rescale(alpha);
         } else {
-            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1);
+            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1, fast_tag);
         }
         wait_copies_and_barrier();
         if (has_next) {
-            decide(nxt, j + 1);
+            decide(nxt, j + 1, fast_tag);
             if (!CALIB && nxt.keep) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v[CALIB ? 0 : ((j + 1) & 1)], wave);
             if (j + 3 < n_blk) tile_copy_async<D, NT>(kbase + (int64_t)(j + 3) * kstep, koff, lds_k[(j + 1) & 1], wave);
         }
@@ -364,15 +382,23 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
     tile_copy_async<D, NT>(kbase, koff, lds_k[0], wave);
     if (1 < n_blk) tile_copy_async<D, NT>(kbase + kstep, koff, lds_k[1], wave);
     wait_copies_and_barrier();
-    compute_scores(ta, lds_k[0], 0);
+    compute_scores(ta, lds_k[0], 0, std::false_type{});
     wait_copies_and_barrier();
-    decide(ta, 0);
+    decide(ta, 0, std::false_type{});
     if (!CALIB && ta.keep) tile_copy_async<D, NT>(vbase, voff, lds_v[0], wave);
     if (2 < n_blk) tile_copy_async<D, NT>(kbase + 2 * kstep, koff, lds_k[0], wave);
 
-    for (int j = 0; j < n_blk; j += 2) {
-        stage(ta, tb, j);
-        if (j + 1 < n_blk) stage(tb, ta, j + 1);
+    // main loop: pairs of stages whose look-ahead block is gateable (causal only), then the rest
+    int j = 0;
+    if (p.causal) {
+        for (; j + 2 < n_gate; j += 2) {
+            stage(ta, tb, j, std::true_type{});
+            stage(tb, ta, j + 1, std::true_type{});
+        }
+    }
+    for (; j < n_blk; j += 2) {
+        stage(ta, tb, j, std::false_type{});
+        if (j + 1 < n_blk) stage(tb, ta, j + 1, std::false_type{});
     }
 
     // ---- statistics ------------------------------------------------------------------------
@@ -383,7 +409,7 @@ __global__ void __launch_bounds__(NW * 64, 2) bsfa_fwd_kernel(const FwdParams p)
     if (p.counts && tid == 0) {
         unsigned long long *c = p.counts + ((int64_t)b * p.hq + h) * 3;
         const int gateable = p.causal ? n_gate : (p.mkv - (own_hi - own_lo));
-        atomicAdd(c + 0, n_skipped);
+        atomicAdd(c + 0, (unsigned long long)n_skipped);
         atomicAdd(c + 1, (unsigned long long)gateable);
         atomicAdd(c + 2, (unsigned long long)n_blk);
     }
@@ -415,7 +441,7 @@ __global__ void zero_counts_kernel(unsigned long long *c, int n)
     if (t < n) c[t] = 0ull;
 }
 
-template <int D, int NW, int QB>
+template <int D, int NW, int QB, int OCC>
 static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
 {
     const int pairs = p.batch * p.hkv;
@@ -426,9 +452,9 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, true>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, true, OCC>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, false>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, false, OCC>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -444,10 +470,16 @@ hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool ca
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
     // the copies address a tile with 32-bit element offsets
     if (p.ksn * 64 > 0x7fffffffLL || p.vsn * 64 > 0x7fffffffLL) return hipErrorInvalidValue;
-#define BSFA_CASE(DD, NN, QQ) \
-    if (head_dim == DD && block_m == 32 * NN * QQ) return launch_t<DD, NN, QQ>(p, calib, stream);
-    BSFA_CASE(64, 1, 1) BSFA_CASE(64, 2, 1) BSFA_CASE(64, 4, 1)
-    BSFA_CASE(128, 1, 1) BSFA_CASE(128, 2, 1) BSFA_CASE(128, 4, 1)
+#define BSFA_CASE(DD, NN, QQ, OO) \
+    if (head_dim == DD && block_m == 32 * NN * QQ) return launch_t<DD, NN, QQ, OO>(p, calib, stream);
+    {
+        const char *v = getenv("BSFA_VARIANT");
+        const int variant = v ? atoi(v) : 0;
+        if (variant == 1) { BSFA_CASE(128, 4, 1, 1) }
+        if (variant == 2) { BSFA_CASE(128, 2, 2, 1) }
+    }
+    BSFA_CASE(64, 1, 1, 1) BSFA_CASE(64, 2, 1, 1) BSFA_CASE(64, 4, 1, 2)
+    BSFA_CASE(128, 1, 1, 1) BSFA_CASE(128, 2, 1, 1) BSFA_CASE(128, 4, 1, 1)
 #undef BSFA_CASE
     return hipErrorInvalidValue;
 }
