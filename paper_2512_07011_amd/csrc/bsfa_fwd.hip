@@ -1,25 +1,28 @@
 // Block-Sparse FlashAttention forward kernel for gfx950 (MI355X), wave64, bf16 MFMA.
 //
-// One workgroup = one query tile Q_i (B_M = 32 * QB * NW rows: NW waves, QB 32-row column blocks
-// per wave) of one head; it walks the reachable key blocks j in ascending order (Algorithm 1):
+// One workgroup = one query tile Q_i (B_M = 32 * NWH rows, NWH waves of 32 rows) of HP query heads
+// that share a KV head (GQA); it walks the reachable key blocks j in ascending order (Algorithm 1):
 //   S_ij^T = K_j Q_i^T        32x32x16 bf16 MFMA, fp32 accumulate                 (Eq. 5)
 //   s_max  = max S_ij         lane max -> wave max -> cross-wave max through LDS   (Eq. 6)
 //   gate   : s_max / sqrt(d) >= T keeps the block; blocks touching the causal boundary bypass
-//            the gate (Section 4.1).  The decision is workgroup-uniform.
-//   kept   : V_j is requested only after the decision, exp2-based online softmax,
-//            O^T += V_j^T P^T.
+//            the gate (Section 4.1).  One decision per (head, query tile, key block).
+//   kept   : V_j is requested only after the decision (and only if some head of the group keeps
+//            the block), exp2-based online softmax, O^T += V_j^T P^T.
 // The transposed products keep everything of one query row inside one lane pair (l, l^32):
 // the S^T accumulator layout (column = query) is already the B-operand layout of the second
 // MFMA up to a permutation of the keys, and the same permutation is applied to V when its
 // A operand is gathered from LDS with the transposing read, so P never leaves registers.
 //
-// Software pipeline (one barrier per key block).  While block j is being finished the scores
-// of block j+1 are already computed, so its gate decision is known one block ahead:
-//   iteration j:  S_{j+1} = K_{j+1} Q^T  (MFMA)   overlapped with   softmax(S_j)  (VALU)
-//                 block max of S_{j+1} -> LDS;  wait for own global->LDS copies;  barrier
-//                 decide keep_{j+1};  request V_{j+1} (only if kept) and K_{j+3}
-//                 O^T += V_j^T P_j^T   (MFMA, V_j landed before the barrier)
-// K and V tiles go HBM -> LDS directly (no register staging), two buffers each.
+// Software pipeline, one barrier per key block.  The scores of block j+1 are computed while block
+// j is finished, so the gate decision is known one block ahead:
+//   stage j:  softmax(S_j) -> P_j          (VALU)
+//             S_{j+1} = K_{j+1} Q^T        (MFMA), block max of S_{j+1} -> LDS
+//             wait for the copies needed next; barrier
+//             decide keep_{j+1}; request V_{j+1} (only if kept) and K_{j+KR+1}
+//             O^T += V_j^T P_j^T           (MFMA)
+// K tiles sit in a ring of KR LDS slots and are requested KR+1 blocks ahead, V tiles in two slots;
+// both go HBM -> LDS directly, and the waits are partial (vmcnt) so that only the tile needed
+// next has to have landed.
 #include "bsfa_internal.h"
 
 #include <math.h>
@@ -35,14 +38,16 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(uintptr_t)(p))
 #define GLB_PTR(T, p) ((const __attribute__((address_space(1))) T *)(p))
 
 // ---- LDS tile layout --------------------------------------------------------------------
 // A K or V tile is 64 rows x D bf16, stored as 16-byte chunks, row-major, the chunk index
 // XOR-ed with a function of the row so that the operand gathers spread over the banks.  The
 // swizzle is applied on the global side of the copy (lane -> which chunk it fetches); the LDS
-// side of a direct copy is always linear (wave base + lane * 16 bytes).
+// side of a direct copy is always linear (wave base + lane * 16 bytes).  Both swizzles only
+// touch chunk bits that the gather loops step through with XOR-able constants, so every
+// operand address is  (per-lane base) ^ (loop constant) + (immediate offset).
 template <int D> __device__ __forceinline__ int swz_k(int row)
 {
     return (D == 128) ? (row & 15) : ((row >> 1) & 7);
@@ -64,15 +69,40 @@ __device__ __forceinline__ int chunk_src_offset(int r, int tid, int stride_n)
     return row * stride_n + 8 * c;
 }
 
-// Asynchronous HBM -> LDS copy of one 64 x D tile (completion is tracked by vmcnt).
+// Asynchronous HBM -> LDS copy of one 64 x D tile; lds_tile is the byte address of the tile's
+// slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  Completion is
+// tracked by vmcnt, which this kernel manages itself (wait_vmcnt): the instruction is emitted
+// through inline asm so that the compiler does not serialise every later LDS read behind all
+// copies in flight.
 template <int D, int NT>
 __device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const int (&off)[64 * (D / 8) / NT],
-                                                uint16_t *lds_tile, int wave)
+                                                uint32_t lds_tile, int wave)
 {
 #pragma unroll
-    for (int r = 0; r < 64 * (D / 8) / NT; ++r)
-        __builtin_amdgcn_global_load_lds(GLB_PTR(void, gtile + off[r]),
-                                         LDS_PTR(void, lds_tile + (r * NT + wave * 64) * 8), 16, 0, 0);
+    for (int r = 0; r < 64 * (D / 8) / NT; ++r) {
+        const uint16_t *src = gtile + off[r];
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(dst), "v"(src)
+                     : "memory");
+    }
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// Workgroup barrier that orders LDS traffic only: the global -> LDS copies in flight are tracked
+// separately with wait_vmcnt, so the barrier must not drain them.
+__device__ __forceinline__ void wg_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
@@ -104,60 +134,77 @@ __device__ __forceinline__ float wave_max_paired(float x)
                  __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)));
 }
 
-// Work decomposition.  With at least 8 (batch, KV head) pairs the pair is chosen by the low
-// three bits of the workgroup id, which is the XCD the hardware dispatches the group to, so
-// that all groups streaming one K/V sequence share one L2.  Heavy (late) query tiles first.
-__device__ __forceinline__ bool decode_work(const FwdParams &p, int w, int &b, int &h, int &i)
+// Work decomposition: a work item is (batch b, KV head, group of HP query heads, query tile i).
+// With at least 8 (batch, KV head) pairs the pair is chosen by the low three bits of the
+// workgroup id, which is the XCD the hardware dispatches the group to, so that all groups
+// streaming one K/V sequence share one L2.  Heavy (late) query tiles first.
+template <int HP>
+__device__ __forceinline__ bool decode_work(const FwdParams &p, int w, int &b, int &h0, int &i)
 {
     const int pairs = p.batch * p.hkv;
+    const int gsub = p.group / HP;               // head groups per KV head
+    int pair, hg, idesc;
     if (pairs >= 8) {
         const int x = w & 7, r = w >> 3;
         const int npx = (pairs + 7) >> 3;
-        const int per_tile = npx * p.group;
-        const int idesc = r / per_tile, rest = r - idesc * per_tile;
-        const int pl = rest / p.group, hg = rest - pl * p.group;
-        const int pair = x + 8 * pl;
+        const int per_tile = npx * gsub;
+        idesc = r / per_tile;
+        const int rest = r - idesc * per_tile;
+        const int pl = rest / gsub;
+        hg = rest - pl * gsub;
+        pair = x + 8 * pl;
         if (pair >= pairs) return false;
-        b = pair / p.hkv;
-        h = (pair - b * p.hkv) * p.group + hg;
-        i = p.mq - 1 - idesc;
     } else {
-        const int per_tile = p.batch * p.hq;
-        const int idesc = w / per_tile, rest = w - idesc * per_tile;
-        b = rest / p.hq;
-        h = rest - b * p.hq;
-        i = p.mq - 1 - idesc;
+        const int per_tile = pairs * gsub;
+        idesc = w / per_tile;
+        const int rest = w - idesc * per_tile;
+        pair = rest / gsub;
+        hg = rest - pair * gsub;
     }
+    b = pair / p.hkv;
+    h0 = (pair - b * p.hkv) * p.group + hg * HP;
+    i = p.mq - 1 - idesc;
     return true;
 }
 
-template <int QB> struct ScoreTile {
-    f32x16 s[2][QB];      // S^T: [32-key half][32-query column block], raw q.k (no 1/sqrt(d))
-    float mx[QB];         // row max of the lane's query, equal in lanes l and l^32
-    bool keep;            // workgroup-uniform gate decision
+struct ScoreTile {
+    f32x16 s[2];          // S^T: [32-key half], raw q.k (no 1/sqrt(d)); column = this lane's query
+    float mx;             // row max of the lane's query, equal in lanes l and l^32
+    bool keep;            // gate decision of this wave's head (uniform over the head's waves)
+    bool any_keep;        // some head of the workgroup keeps the block (workgroup-uniform): V is fetched
 };
 
-template <int D, int NW, int QB, bool CALIB, int OCC>
-__global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams p)
+template <int D, int NWH, int HP, int KR, bool CALIB>
+__global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdParams p)
 {
+    constexpr int NW = NWH * HP;
     constexpr int NT = NW * 64;
-    constexpr int BM = NW * QB * 32;
+    constexpr int BM = NWH * 32;
     constexpr int BN = kBlockN;
     constexpr int KS = D / 16;       // MFMA k-steps over the head dim
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int CPR = D / 8;       // 16-byte chunks per tile row
     constexpr int NST = 64 * CPR / NT;
+    constexpr int TILE_BYTES = BN * D * 2;
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int R = KR + 1;        // K tiles are requested R blocks ahead
+    constexpr int VR = CALIB ? 0 : 2;
+    static_assert(NST >= 1 && (R < 4 || NST * (R - 3) < 64), "copy repetitions");
 
-    __shared__ __attribute__((aligned(1024))) uint16_t lds_k[2][BN * D];
-    __shared__ __attribute__((aligned(1024))) uint16_t lds_v[CALIB ? 1 : 2][CALIB ? 8 : BN * D];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[(KR + VR) * TILE_BYTES];
     __shared__ float lds_red[2][NW];
+    const uint32_t lds_k0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
+    const uint32_t lds_v0 = lds_k0 + KR * TILE_BYTES;
 
-    int b, h, i;
-    if (!decode_work(p, blockIdx.x, b, h, i)) return;
+    int b, h0, i;
+    if (!decode_work<HP>(p, blockIdx.x, b, h0, i)) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hsel = wave / NWH, wrow = wave % NWH;      // which head of the group, which 32-row slice
+    const int h = h0 + hsel;
     const int l32 = lane & 31, hh = lane >> 5;
-    const int g = h / p.group;
+    const int g = h0 / p.group;
+    const bool stat_lane = (wrow == 0 && lane == 0);     // one lane per head writes statistics
 
     const int64_t row0 = (int64_t)i * BM;                 // first query row of the tile
     const int n_blk = p.causal ? (int)((row0 + BM + BN - 1) / BN) : p.mkv;   // reachable blocks
@@ -168,7 +215,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams 
 
     const uint16_t *kbase = p.k + (int64_t)b * p.ksb + (int64_t)g * p.ksh;
     const uint16_t *vbase = p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
-    const float tau = p.tau[p.tau_per_tile ? (int64_t)h * p.mq + i : h];
+    float tau_h[HP];                                      // thresholds of the group's heads for this tile
+#pragma unroll
+    for (int x = 0; x < HP; ++x) tau_h[x] = p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.mq + i : (h0 + x)];
 
     int koff[NST], voff[NST];
 #pragma unroll
@@ -178,59 +227,60 @@ __global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams 
     }
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
 
-    // Q_i^T as the B operand: lane holds query (wave*32*QB + 32*qb + l32), head-dim slice 16s + 8hh .. +7
-    bf16x8 qreg[QB][KS];
-    int q_row[QB];
+    // Operand gather addresses (bytes inside a tile slot).
+    // K (A operand of S^T): lane reads key row 32*kb + l32, chunk (2s + hh) ^ swz_k(row).  The row
+    // swizzle does not depend on kb (32 is a multiple of its period) and 2s only occupies chunk
+    // bits 1.., so  addr(s, kb) = (ka_base ^ (s << 5)) + kb * 32 * ROW_BYTES.
+    const uint32_t ka_base = (uint32_t)(l32 * ROW_BYTES + ((hh ^ swz_k<D>(l32)) << 4));
+    // V (A operand of O^T, transposing read of 4 keys x 16 head-dim columns per 16 lanes): lane
+    // reads row 16u + 4hh + (L >> 2) (+8 for the second half), 8 bytes at element column
+    // 32x + 16*g16 + 4*(L & 3).  The row swizzle has period 8 rows, so it does not depend on u or
+    // the +8, and x only occupies chunk bits 2.., so
+    // addr(u, x, half) = (va_base ^ (x << 6)) + (16u + 8*half) * ROW_BYTES.
+    const int L = lane & 15, g16 = (lane >> 4) & 1;
+    const int vrow = 4 * hh + (L >> 2);
+    const int vcol = 16 * g16 + 4 * (L & 3);
+    const uint32_t va_base = (uint32_t)(vrow * ROW_BYTES + (((vcol >> 3) ^ swz_v<D>(vrow)) << 4) + ((vcol >> 2) & 1) * 8);
+
+    // Q_i^T as the B operand: lane holds query (32*wrow + l32), head-dim slice 16s + 8hh .. +7
+    bf16x8 qreg[KS];
+    const int q_row = (int)row0 + wrow * 32 + l32;
+    {
+        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)q_row * p.qsn + (int64_t)h * p.qsh + 8 * hh;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        q_row[qb] = (int)row0 + (wave * QB + qb) * 32 + l32;
-        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)q_row[qb] * p.qsn + (int64_t)h * p.qsh + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     }
 
-    f32x16 oacc[DB][QB];
+    f32x16 oacc[DB];
 #pragma unroll
     for (int x = 0; x < DB; ++x)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[x][qb][e] = 0.f;
-    float m_run[QB], l_run[QB];    // running row max (log2 units) and this lane's share of the normaliser
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-    }
+        for (int e = 0; e < 16; ++e) oacc[x][e] = 0.f;
+    float m_run = -INFINITY;   // running row max, log2 units (score * log2(e)/sqrt(d))
+    float l_run = 0.f;         // this lane's share of the running normaliser
 
-    unsigned n_skipped = 0;      // workgroup-uniform statistics
+    unsigned n_skipped = 0;    // per-head statistics, uniform over the head's waves
     uint32_t mask_word = 0;
     const int64_t stat_row = ((int64_t)b * p.hq + h) * p.mq + i;
 
     auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
-    // S^T of block j from the K tile in `kt`, row maxima, and the wave's block maximum into
-    // lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask, always reduced),
-    // which keeps the whole function free of branches.
-    auto compute_scores = [&](ScoreTile<QB> &t, const uint16_t *kt, int j, auto fast_tag) {
+    // S^T of block j from the K tile at LDS byte address `kt`, row maxima, and the wave's block
+    // maximum into lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask).
+    auto compute_scores = [&](ScoreTile &t, uint32_t kt, int j, auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) t.s[kb][qb][e] = 0.f;
-        }
+            for (int e = 0; e < 16; ++e) t.s[kb][e] = 0.f;
+        const uint32_t kaddr = kt + ka_base;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
+            const uint32_t a_s = kaddr ^ (uint32_t)(s << 5);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const int row = 32 * kb + l32;
-                const int c = (2 * s + hh) ^ swz_k<D>(row);
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kt + (row * CPR + c) * 8);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    t.s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], t.s[kb][qb], 0, 0, 0);
+                const bf16x8 a = *LDS_PTR(const bf16x8, a_s + kb * 32 * ROW_BYTES);
+                t.s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], t.s[kb], 0, 0, 0);
             }
         }
         const bool gated = FAST ? true : is_gated(j);
@@ -239,154 +289,146 @@ __global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams 
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
-                            if (key > q_row[qb]) t.s[kb][qb][e] = -INFINITY;
-                        }
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = j * BN + 32 * kb + 8 * (e >> 2) + 4 * hh + (e & 3);
+                        if (key > q_row) t.s[kb][e] = -INFINITY;
+                    }
             }
         }
-        float all = -INFINITY;
+        float mx = -INFINITY;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float mx = -INFINITY;
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t.s[kb][qb][e]);
-            t.mx[qb] = pair_max(mx);
-            all = fmaxf(all, t.mx[qb]);
-        }
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t.s[kb][e]);
+        t.mx = pair_max(mx);
         if (gated) {
-            const float wm = wave_max_paired(all);
+            const float wm = wave_max_paired(t.mx);
             if (lane == 0) lds_red[j & 1][wave] = wm;
         }
     };
 
-    // gate decision for block j (after the barrier that publishes lds_red[j & 1]) + statistics
-    auto decide = [&](ScoreTile<QB> &t, int j, auto fast_tag) {
+    // gate decisions for block j (after the barrier that publishes lds_red[j & 1]) + statistics
+    auto decide = [&](ScoreTile &t, int j, auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
-        bool keep = true;
+        bool keep = true, any_keep = true;
         float bmax = NAN;
         if (FAST || is_gated(j)) {
-            float r = lds_red[j & 1][0];
+            any_keep = false;
 #pragma unroll
-            for (int w = 1; w < NW; ++w) r = fmaxf(r, lds_red[j & 1][w]);
-            bmax = r * p.scale;                          // natural score units (Eq. 5-6)
-            keep = (bmax >= tau);                        // skip iff s_max < T
+            for (int x = 0; x < HP; ++x) {
+                float r = lds_red[j & 1][x * NWH];
+#pragma unroll
+                for (int w = 1; w < NWH; ++w) r = fmaxf(r, lds_red[j & 1][x * NWH + w]);
+                const float sm = r * p.scale;                        // natural score units (Eq. 5-6)
+                const bool kx = (sm >= tau_h[x]);                    // skip iff s_max < T
+                any_keep = any_keep || kx;
+                if (x == hsel) {
+                    keep = kx;
+                    bmax = sm;
+                }
+            }
         }
         t.keep = keep;
+        t.any_keep = any_keep;
         n_skipped += keep ? 0 : 1;
         mask_word |= (keep ? 0u : 1u) << (j & 31);
-        if (p.block_max && tid == 0) p.block_max[stat_row * p.mkv + j] = bmax;
+        if (p.block_max && stat_lane) p.block_max[stat_row * p.mkv + j] = bmax;
         if ((j & 31) == 31 || j == n_blk - 1) {
-            if (p.skip_mask && tid == 0) p.skip_mask[stat_row * p.mask_words + (j >> 5)] = mask_word;
+            if (p.skip_mask && stat_lane) p.skip_mask[stat_row * p.mask_words + (j >> 5)] = mask_word;
             mask_word = 0;
         }
     };
 
-    // online-softmax update of the running statistics with block `t`; P (bf16) into pb; returns
-    // in alpha[] the factor the accumulator still has to be multiplied with
-    auto softmax = [&](ScoreTile<QB> &t, bf16x8 (&pb)[4][QB], float (&alpha)[QB]) {
+    // online-softmax update of the running statistics with block `t`; P (bf16) into pb; the
+    // accumulator is rescaled here (the previous block's PV has been issued already)
+    auto softmax = [&](ScoreTile &t, bf16x8 (&pb)[4]) {
+        const float m_new = fmaxf(m_run, t.mx * p.scale_log2);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float m_new = fmaxf(m_run[qb], t.mx[qb] * p.scale_log2);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
-            m_run[qb] = m_new;
-            float psum = 0.f;
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float pe = __builtin_amdgcn_exp2f(fmaf(t.s[kb][qb][e], p.scale_log2, -m_use));
-                    t.s[kb][qb][e] = pe;
-                    psum += pe;
-                }
-            l_run[qb] = l_run[qb] * alpha[qb] + psum;
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pb[u][qb][e] = (__bf16)t.s[u >> 1][qb][8 * (u & 1) + e];
-        }
-    };
-
-    auto rescale = [&](const float (&alpha)[QB]) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            if (__any(alpha[qb] != 1.0f)) {
-#pragma unroll
-                for (int x = 0; x < DB; ++x)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[x][qb][e] *= alpha[qb];
+            for (int e = 0; e < 16; ++e) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e], p.scale_log2, -m_use));
+                t.s[kb][e] = pe;
+                psum += pe;
             }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pb[u][e] = (__bf16)t.s[u >> 1][8 * (u & 1) + e];
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int x = 0; x < DB; ++x)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[x][e] *= alpha;
         }
     };
 
-    // O^T += V^T P^T for the V tile in `vt`
-    auto pv = [&](const bf16x8 (&pb)[4][QB], const uint16_t *vt) {
-        const int L = lane & 15, g16 = (lane >> 4) & 1;
+    // O^T += V^T P^T for the V tile at LDS byte address `vt`
+    auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt) {
+        const uint32_t vaddr = vt + va_base;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {                     // 16 keys per MFMA k-step
-            const int r0 = 16 * u + 4 * hh + (L >> 2);
-            const int r1 = r0 + 8;
 #pragma unroll
             for (int x = 0; x < DB; ++x) {
-                const int dcol = 32 * x + 16 * g16 + 4 * (L & 3);         // element column
-                const int c = dcol >> 3, half = (dcol >> 2) & 1;
-                const uint16_t *a0 = vt + (r0 * CPR + (c ^ swz_v<D>(r0))) * 8 + 4 * half;
-                const uint16_t *a1 = vt + (r1 * CPR + (c ^ swz_v<D>(r1))) * 8 + 4 * half;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a1));
+                const uint32_t a_x = (vaddr ^ (uint32_t)(x << 6)) + u * 16 * ROW_BYTES;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x + 8 * ROW_BYTES));
                 const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    oacc[x][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[u][qb], oacc[x][qb], 0, 0, 0);
+                oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[u], oacc[x], 0, 0, 0);
             }
         }
-    };
-
-    auto wait_copies_and_barrier = [&]() {
-        __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt(0): this wave's HBM -> LDS copies have landed
-        __syncthreads();
     };
 
     // One pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`).
     // FAST: block j+1 exists and is gateable, so the look-ahead has no mask and no conditionals.
-    auto stage = [&](ScoreTile<QB> &cur, ScoreTile<QB> &nxt, int j, auto fast_tag) {
+    auto stage = [&](ScoreTile &cur, ScoreTile &nxt, int j, auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         const bool has_next = FAST || (j + 1 < n_blk);
-        bf16x8 pb[4][QB];
-        float alpha[QB];
-        if (!CALIB && cur.keep) {
-            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1, fast_tag);
-            softmax(cur, pb, alpha);
-            rescale(alpha);
+        bf16x8 pb[4];
+        const bool do_pv = !CALIB && cur.keep;
+        if (do_pv) softmax(cur, pb);
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) compute_scores(nxt, lds_k0 + (uint32_t)((j + 1) % KR) * TILE_BYTES, j + 1, fast_tag);
+        // copies that must have landed before the barrier: V_j (if requested) and K_{j+2}; every
+        // younger request (K_{j+3} .. K_{j+R-1}, issued after V_j) may stay in flight
+        if (R >= 4 && j - 1 + R < n_blk) {
+            if (!CALIB && cur.any_keep) wait_vmcnt<NST>();
+            else wait_vmcnt<(R >= 4 ? NST * (R - 3) : 0)>();
         } else {
-            if (has_next) compute_scores(nxt, lds_k[(j + 1) & 1], j + 1, fast_tag);
+            wait_vmcnt<0>();
         }
-        wait_copies_and_barrier();
+        wg_barrier();
         if (has_next) {
             decide(nxt, j + 1, fast_tag);
-            if (!CALIB && nxt.keep) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v[CALIB ? 0 : ((j + 1) & 1)], wave);
-            if (j + 3 < n_blk) tile_copy_async<D, NT>(kbase + (int64_t)(j + 3) * kstep, koff, lds_k[(j + 1) & 1], wave);
+            if (!CALIB && nxt.any_keep)
+                tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
+            if (j + R < n_blk)
+                tile_copy_async<D, NT>(kbase + (int64_t)(j + R) * kstep, koff, lds_k0 + (uint32_t)((j + R) % KR) * TILE_BYTES, wave);
         }
         if constexpr (!CALIB) {
-            if (cur.keep) pv(pb, lds_v[j & 1]);
+            if (do_pv) pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES);
         }
     };
 
-    // ---- prologue: K_0, K_1 in flight, scores and decision of block 0 -------------------------
-    ScoreTile<QB> ta, tb;
-    tile_copy_async<D, NT>(kbase, koff, lds_k[0], wave);
-    if (1 < n_blk) tile_copy_async<D, NT>(kbase + kstep, koff, lds_k[1], wave);
-    wait_copies_and_barrier();
-    compute_scores(ta, lds_k[0], 0, std::false_type{});
-    wait_copies_and_barrier();
+    // ---- prologue: scores and decision of block 0, then K_1 .. K_{R-1} and V_0 -----------------
+    ScoreTile ta, tb;
+    tile_copy_async<D, NT>(kbase, koff, lds_k0, wave);
+    wait_vmcnt<0>();
+    wg_barrier();
+    compute_scores(ta, lds_k0, 0, std::false_type{});
+    wg_barrier();                                       // block maxima visible, K_0 consumed
     decide(ta, 0, std::false_type{});
-    if (!CALIB && ta.keep) tile_copy_async<D, NT>(vbase, voff, lds_v[0], wave);
-    if (2 < n_blk) tile_copy_async<D, NT>(kbase + 2 * kstep, koff, lds_k[0], wave);
+    if (!CALIB && ta.any_keep) tile_copy_async<D, NT>(vbase, voff, lds_v0, wave);
+#pragma unroll
+    for (int t = 1; t < R; ++t)                            // K_{R-1} reuses the slot block 0 has just left
+        if (t < n_blk) tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, lds_k0 + (uint32_t)(t % KR) * TILE_BYTES, wave);
+    wait_vmcnt<0>();                                       // drained once; from here on the steady-state rule holds
+    wg_barrier();
 
     // main loop: pairs of stages whose look-ahead block is gateable (causal only), then the rest
     int j = 0;
@@ -402,11 +444,12 @@ __global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams 
     }
 
     // ---- statistics ------------------------------------------------------------------------
+    const int htid = tid - hsel * NWH * 64;               // thread index within the head's waves
     if (p.block_max)
-        for (int j = n_blk + tid; j < p.mkv; j += NT) p.block_max[stat_row * p.mkv + j] = NAN;
+        for (int jj = n_blk + htid; jj < p.mkv; jj += NWH * 64) p.block_max[stat_row * p.mkv + jj] = NAN;
     if (p.skip_mask)
-        for (int w = ((n_blk + 31) >> 5) + tid; w < p.mask_words; w += NT) p.skip_mask[stat_row * p.mask_words + w] = 0u;
-    if (p.counts && tid == 0) {
+        for (int w = ((n_blk + 31) >> 5) + htid; w < p.mask_words; w += NWH * 64) p.skip_mask[stat_row * p.mask_words + w] = 0u;
+    if (p.counts && stat_lane) {
         unsigned long long *c = p.counts + ((int64_t)b * p.hq + h) * 3;
         const int gateable = p.causal ? n_gate : (p.mkv - (own_hi - own_lo));
         atomicAdd(c + 0, (unsigned long long)n_skipped);
@@ -416,22 +459,19 @@ __global__ void __launch_bounds__(NW * 64, OCC) bsfa_fwd_kernel(const FwdParams 
 
     // ---- O_i = O~_i / l_i, written as bf16 ----------------------------------------------------
     if constexpr (!CALIB) {
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        const float inv = 1.0f / l_tot;
+        uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row * p.osn + (int64_t)h * p.osh;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-            const float inv = 1.0f / l_tot;
-            uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row[qb] * p.osn + (int64_t)h * p.osh;
+        for (int x = 0; x < DB; ++x)
 #pragma unroll
-            for (int x = 0; x < DB; ++x)
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int d0 = 32 * x + 8 * e4 + 4 * hh;
+                bf16x4 o;
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int d0 = 32 * x + 8 * e4 + 4 * hh;
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][qb][4 * e4 + e] * inv);
-                    *reinterpret_cast<bf16x4 *>(op + d0) = o;
-                }
-        }
+                for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][4 * e4 + e] * inv);
+                *reinterpret_cast<bf16x4 *>(op + d0) = o;
+            }
     }
 }
 
@@ -441,20 +481,21 @@ __global__ void zero_counts_kernel(unsigned long long *c, int n)
     if (t < n) c[t] = 0ull;
 }
 
-template <int D, int NW, int QB, int OCC>
+template <int D, int NWH, int HP, int KR>
 static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
 {
     const int pairs = p.batch * p.hkv;
-    long grid = (pairs >= 8) ? 8L * ((pairs + 7) / 8) * p.group * p.mq : (long)p.batch * p.hq * p.mq;
+    const int gsub = p.group / HP;
+    long grid = (pairs >= 8) ? 8L * ((pairs + 7) / 8) * gsub * p.mq : (long)pairs * gsub * p.mq;
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
     if (p.counts) {
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, true, OCC>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NW, QB, false, OCC>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -470,16 +511,18 @@ hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool ca
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
     // the copies address a tile with 32-bit element offsets
     if (p.ksn * 64 > 0x7fffffffLL || p.vsn * 64 > 0x7fffffffLL) return hipErrorInvalidValue;
-#define BSFA_CASE(DD, NN, QQ, OO) \
-    if (head_dim == DD && block_m == 32 * NN * QQ) return launch_t<DD, NN, QQ, OO>(p, calib, stream);
-    {
-        const char *v = getenv("BSFA_VARIANT");
-        const int variant = v ? atoi(v) : 0;
-        if (variant == 1) { BSFA_CASE(128, 4, 1, 1) }
-        if (variant == 2) { BSFA_CASE(128, 2, 2, 1) }
+    const char *ev = getenv("BSFA_VARIANT");
+    const int variant = ev ? atoi(ev) : 0;
+    const bool pair_heads = (p.group % 2 == 0) && variant != 1;
+#define BSFA_CASE(DD, NN, HH, KK) \
+    if (head_dim == DD && block_m == 32 * NN) return launch_t<DD, NN, HH, KK>(p, calib, stream);
+    if (pair_heads) {
+        // two query heads of a GQA group per workgroup: one K/V stream in LDS feeds both
+        BSFA_CASE(128, 4, 2, 5)
+        BSFA_CASE(64, 4, 2, 5)
     }
-    BSFA_CASE(64, 1, 1, 1) BSFA_CASE(64, 2, 1, 1) BSFA_CASE(64, 4, 1, 2)
-    BSFA_CASE(128, 1, 1, 1) BSFA_CASE(128, 2, 1, 1) BSFA_CASE(128, 4, 1, 1)
+    BSFA_CASE(64, 1, 1, 2) BSFA_CASE(64, 2, 1, 2) BSFA_CASE(64, 4, 1, 3)
+    BSFA_CASE(128, 1, 1, 2) BSFA_CASE(128, 2, 1, 2) BSFA_CASE(128, 4, 1, 2)
 #undef BSFA_CASE
     return hipErrorInvalidValue;
 }
