@@ -265,10 +265,8 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
-    // S^T of block j from the K tile at LDS byte address `kt`, row maxima, and the wave's block
-    // maximum into lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask).
-    auto compute_scores = [&](ScoreTile &t, uint32_t kt, int j, auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
+    // S^T of block j from the K tile at LDS byte address `kt` (MFMA and LDS reads only)
+    auto qk_mfma = [&](ScoreTile &t, uint32_t kt) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -283,6 +281,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                 t.s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], t.s[kb], 0, 0, 0);
             }
         }
+    };
+
+    // causal mask on boundary blocks, row maxima, and the wave's block maximum into
+    // lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask).
+    auto reduce_scores = [&](ScoreTile &t, int j, auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
         const bool gated = FAST ? true : is_gated(j);
         if constexpr (!FAST) {
             if (p.causal && !gated) {
@@ -339,13 +343,16 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         }
     };
 
-    // online-softmax update of the running statistics with block `t`; P (bf16) into pb; the
-    // accumulator is rescaled here (the previous block's PV has been issued already)
-    auto softmax = [&](ScoreTile &t, bf16x8 (&pb)[4]) {
+    // online-softmax update of the running statistics with block `t`: new row max and the
+    // accumulator's rescale factor first, then the exponentials, P (bf16) into pb
+    auto softmax_begin = [&](ScoreTile &t, float &m_use) -> float {
         const float m_new = fmaxf(m_run, t.mx * p.scale_log2);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
         m_run = m_new;
+        return alpha;
+    };
+    auto softmax_exp = [&](ScoreTile &t, float m_use, float alpha, bf16x8 (&pb)[4]) {
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -360,6 +367,46 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int e = 0; e < 8; ++e) pb[u][e] = (__bf16)t.s[u >> 1][8 * (u & 1) + e];
+    };
+    // softmax_exp(cur) and qk_mfma(nxt) fused.  The exponentials of block j and the score MFMAs
+    // of block j+1 are independent: they are written interleaved (per MFMA a few exponentials,
+    // their row-sum adds and bf16 packs) and pinned in that order, so that the matrix pipe and
+    // the VALU run together.  K operands are read two MFMAs ahead.
+    auto fused_exp_qk = [&](ScoreTile &cur, ScoreTile &nxt, uint32_t kt, float m_use, float alpha, bf16x8 (&pb)[4]) {
+        const uint32_t kaddr = kt + ka_base;
+        auto k_operand = [&](int n) {
+            const uint32_t a_s = kaddr ^ (uint32_t)((n >> 1) << 5);
+            return *LDS_PTR(const bf16x8, a_s + (n & 1) * 32 * ROW_BYTES);
+        };
+        bf16x8 a[2 * KS + 2];
+        a[0] = k_operand(0);
+        a[1] = k_operand(1);
+        float psum0 = 0.f, psum1 = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) nxt.s[kb][e] = 0.f;
+        constexpr int EPM = 32 / (2 * KS);         // exponentials per MFMA (2 at D = 128, 4 at D = 64)
+#pragma unroll
+        for (int n = 0; n < 2 * KS; ++n) {
+            if (n + 2 < 2 * KS) a[n + 2] = k_operand(n + 2);
+            nxt.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], nxt.s[n & 1], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < EPM; t += 2) {
+                const int idx = n * EPM + t, kb = idx >> 4, e = idx & 15;
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e], p.scale_log2, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e + 1], p.scale_log2, -m_use));
+                psum0 += p0;
+                psum1 += p1;
+                pb[idx >> 3][idx & 7] = (__bf16)p0;
+                pb[idx >> 3][(idx & 7) + 1] = (__bf16)p1;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        l_run = l_run * alpha + (psum0 + psum1);
+    };
+
+    auto rescale = [&](float alpha) {
         if (__any(alpha != 1.0f)) {
 #pragma unroll
             for (int x = 0; x < DB; ++x)
@@ -391,9 +438,21 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const bool has_next = FAST || (j + 1 < n_blk);
         bf16x8 pb[4];
         const bool do_pv = !CALIB && cur.keep;
-        if (do_pv) softmax(cur, pb);
-        __builtin_amdgcn_sched_barrier(0);
-        if (has_next) compute_scores(nxt, lds_k0 + (uint32_t)((j + 1) % KR) * TILE_BYTES, j + 1, fast_tag);
+        const uint32_t kt_next = lds_k0 + (uint32_t)((j + 1) % KR) * TILE_BYTES;
+        if (do_pv) {
+            float m_use;
+            const float alpha = softmax_begin(cur, m_use);
+            rescale(alpha);                       // the previous block's PV has been issued already
+            if constexpr (FAST) {
+                fused_exp_qk(cur, nxt, kt_next, m_use, alpha, pb);
+            } else {
+                softmax_exp(cur, m_use, alpha, pb);
+                if (has_next) qk_mfma(nxt, kt_next);
+            }
+        } else {
+            if (has_next) qk_mfma(nxt, kt_next);
+        }
+        if (has_next) reduce_scores(nxt, j + 1, fast_tag);
         // copies that must have landed before the barrier: V_j (if requested) and K_{j+2}; every
         // younger request (K_{j+3} .. K_{j+R-1}, issued after V_j) may stay in flight
         if (R >= 4 && j - 1 + R < n_blk) {
@@ -420,7 +479,8 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     tile_copy_async<D, NT>(kbase, koff, lds_k0, wave);
     wait_vmcnt<0>();
     wg_barrier();
-    compute_scores(ta, lds_k0, 0, std::false_type{});
+    qk_mfma(ta, lds_k0);
+    reduce_scores(ta, 0, std::false_type{});
     wg_barrier();                                       // block maxima visible, K_0 consumed
     decide(ta, 0, std::false_type{});
     if (!CALIB && ta.any_keep) tile_copy_async<D, NT>(vbase, voff, lds_v0, wave);
