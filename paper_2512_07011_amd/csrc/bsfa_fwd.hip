@@ -34,6 +34,7 @@ namespace bsfa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -105,12 +106,6 @@ __device__ __forceinline__ void wg_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
-{
-    const int x = __builtin_bit_cast(int, v);
-    return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, 0xf, 0xf, false)));
-}
-
 // max over lanes l and l^32, result in both lanes.  v_permlane32_swap exchanges the upper half
 // of its first operand with the lower half of its second: with two copies of x the first
 // register ends up holding x[l & 31] and the second x[32 + (l & 31)] in every lane.  Written as
@@ -118,17 +113,21 @@ template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
 __device__ __forceinline__ float pair_max(float x)
 {
     float a = x, b;
-    asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "=&v"(b));
-    return fmaxf(a, b);
+    asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
+                 : "+v"(a), "=&v"(b));
+    return a;
 }
 
-// max over the wave of a value that is already equal in lanes l and l^32 (wave-uniform result)
+// max over the wave of a value that is already equal in lanes l and l^32 (wave-uniform result):
+// four DPP steps inside each row of 16 lanes, then rows 0 and 1 are combined through SGPRs.
 __device__ __forceinline__ float wave_max_paired(float x)
 {
-    x = dpp_max<0xB1>(x);     // quad_perm [1,0,3,2]
-    x = dpp_max<0x4E>(x);     // quad_perm [2,3,0,1]
-    x = dpp_max<0x141>(x);    // row_half_mirror
-    x = dpp_max<0x140>(x);    // row_mirror
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1"
+                 : "+v"(x));
     const int xi = __builtin_bit_cast(int, x);
     return fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)),
                  __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)));
@@ -233,13 +232,19 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // bits 1.., so  addr(s, kb) = (ka_base ^ (s << 5)) + kb * 32 * ROW_BYTES.
     const uint32_t ka_base = (uint32_t)(l32 * ROW_BYTES + ((hh ^ swz_k<D>(l32)) << 4));
     // V (A operand of O^T, transposing read of 4 keys x 16 head-dim columns per 16 lanes): lane
-    // reads row 16u + 4hh + (L >> 2) (+8 for the second half), 8 bytes at element column
-    // 32x + 16*g16 + 4*(L & 3).  The row swizzle has period 8 rows, so it does not depend on u or
-    // the +8, and x only occupies chunk bits 2.., so
-    // addr(u, x, half) = (va_base ^ (x << 6)) + (16u + 8*half) * ROW_BYTES.
+    // reads row 16u + 4hh + (L >> 2) (+8 for the second half), 8 bytes.  Which head-dim column an
+    // operand row stands for is free (it only permutes the rows of O^T, undone at the final
+    // store): at D = 128 operand rows 0-15 of block x are columns 16x .. 16x+15 and rows 16-31 are
+    // columns 64+16x .., which puts the two 16-lane groups of a read into different bank halves;
+    // at D = 64 rows 0-31 are columns 32x .. 32x+31.  The row swizzle has period 8 rows, so it does
+    // not depend on u or the +8, and x occupies chunk bits the swizzle only XORs, so
+    // addr(u, x, half) = (va_base ^ (x << XSH)) + (16u + 8*half) * ROW_BYTES.
+    constexpr int G16_COLS = (D == 128) ? 64 : 16;       // column distance of the two 16-lane groups
+    constexpr int X_COLS = (D == 128) ? 16 : 32;         // column step of x
+    constexpr int XSH = (D == 128) ? 5 : 6;              // log2(X_COLS * 2 bytes)
     const int L = lane & 15, g16 = (lane >> 4) & 1;
     const int vrow = 4 * hh + (L >> 2);
-    const int vcol = 16 * g16 + 4 * (L & 3);
+    const int vcol = G16_COLS * g16 + 4 * (L & 3);
     const uint32_t va_base = (uint32_t)(vrow * ROW_BYTES + (((vcol >> 3) ^ swz_v<D>(vrow)) << 4) + ((vcol >> 2) & 1) * 8);
 
     // Q_i^T as the B operand: lane holds query (32*wrow + l32), head-dim slice 16s + 8hh .. +7
@@ -265,21 +270,30 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
-    // S^T of block j from the K tile at LDS byte address `kt` (MFMA and LDS reads only)
+    // K operand n (= k-step n/2, 32-key half n%2) of the tile at LDS byte address kaddr (+ka_base)
+    auto k_operand = [&](uint32_t kaddr, int n) {
+        const uint32_t a_s = kaddr ^ (uint32_t)((n >> 1) << 5);
+        return *LDS_PTR(const bf16x8, a_s + (n & 1) * 32 * ROW_BYTES);
+    };
+    constexpr int PD = 4;            // LDS operand reads are issued PD MFMAs ahead of their use
+
+    // S^T of block j from the K tile at LDS byte address `kt` (MFMA and LDS reads only); the
+    // order reads-ahead / MFMA is pinned so that no MFMA waits for a read issued just before it
     auto qk_mfma = [&](ScoreTile &t, uint32_t kt) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) t.s[kb][e] = 0.f;
         const uint32_t kaddr = kt + ka_base;
+        bf16x8 a[2 * KS + PD];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const uint32_t a_s = kaddr ^ (uint32_t)(s << 5);
+        for (int n = 0; n < PD; ++n) a[n] = k_operand(kaddr, n);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 a = *LDS_PTR(const bf16x8, a_s + kb * 32 * ROW_BYTES);
-                t.s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], t.s[kb], 0, 0, 0);
-            }
+        for (int n = 0; n < 2 * KS; ++n) {
+            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
+            t.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], t.s[n & 1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -354,34 +368,30 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     };
     auto softmax_exp = [&](ScoreTile &t, float m_use, float alpha, bf16x8 (&pb)[4]) {
         float psum = 0.f;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float pe = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e], p.scale_log2, -m_use));
-                t.s[kb][e] = pe;
-                psum += pe;
-            }
+        for (int idx = 0; idx < 32; idx += 2) {
+            const int kb = idx >> 4, e = idx & 15;
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e], p.scale_log2, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e + 1], p.scale_log2, -m_use));
+            const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);   // sum of the rounded values
+            pb[idx >> 3][idx & 7] = pp[0];
+            pb[idx >> 3][(idx & 7) + 1] = pp[1];
+        }
         l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pb[u][e] = (__bf16)t.s[u >> 1][8 * (u & 1) + e];
     };
     // softmax_exp(cur) and qk_mfma(nxt) fused.  The exponentials of block j and the score MFMAs
     // of block j+1 are independent: they are written interleaved (per MFMA a few exponentials,
     // their row-sum adds and bf16 packs) and pinned in that order, so that the matrix pipe and
-    // the VALU run together.  K operands are read two MFMAs ahead.
+    // the VALU run together.  K operands are read PD MFMAs ahead.
     auto fused_exp_qk = [&](ScoreTile &cur, ScoreTile &nxt, uint32_t kt, float m_use, float alpha, bf16x8 (&pb)[4]) {
         const uint32_t kaddr = kt + ka_base;
-        auto k_operand = [&](int n) {
-            const uint32_t a_s = kaddr ^ (uint32_t)((n >> 1) << 5);
-            return *LDS_PTR(const bf16x8, a_s + (n & 1) * 32 * ROW_BYTES);
-        };
-        bf16x8 a[2 * KS + 2];
-        a[0] = k_operand(0);
-        a[1] = k_operand(1);
+        bf16x8 a[2 * KS + PD];
+#pragma unroll
+        for (int n = 0; n < PD; ++n) a[n] = k_operand(kaddr, n);
         float psum0 = 0.f, psum1 = 0.f;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -389,17 +399,19 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         constexpr int EPM = 32 / (2 * KS);         // exponentials per MFMA (2 at D = 128, 4 at D = 64)
 #pragma unroll
         for (int n = 0; n < 2 * KS; ++n) {
-            if (n + 2 < 2 * KS) a[n + 2] = k_operand(n + 2);
+            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
             nxt.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], nxt.s[n & 1], 0, 0, 0);
 #pragma unroll
             for (int t = 0; t < EPM; t += 2) {
                 const int idx = n * EPM + t, kb = idx >> 4, e = idx & 15;
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e], p.scale_log2, -m_use));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e + 1], p.scale_log2, -m_use));
-                psum0 += p0;
-                psum1 += p1;
-                pb[idx >> 3][idx & 7] = (__bf16)p0;
-                pb[idx >> 3][(idx & 7) + 1] = (__bf16)p1;
+                const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+                // row sum of the rounded values (the ones the second MFMA multiplies): p0 + p1 + acc
+                if (t & 2) psum1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum1, false);
+                else psum0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum0, false);
+                pb[idx >> 3][idx & 7] = pp[0];
+                pb[idx >> 3][(idx & 7) + 1] = pp[1];
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -415,19 +427,27 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         }
     };
 
-    // O^T += V^T P^T for the V tile at LDS byte address `vt`
+    // O^T += V^T P^T for the V tile at LDS byte address `vt`; operand n = (k-step u = n / DB,
+    // head-dim block x = n % DB), read PD MFMAs ahead
     auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt) {
         const uint32_t vaddr = vt + va_base;
+        auto v_operand = [&](int n) {
+            const int u = n / DB, x = n % DB;
+            const uint32_t a_x = (vaddr ^ (uint32_t)(x << XSH)) + u * 16 * ROW_BYTES;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x + 8 * ROW_BYTES));
+            const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, av);
+        };
+        bf16x8 a[4 * DB + PD];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {                     // 16 keys per MFMA k-step
+        for (int n = 0; n < PD; ++n) a[n] = v_operand(n);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int x = 0; x < DB; ++x) {
-                const uint32_t a_x = (vaddr ^ (uint32_t)(x << 6)) + u * 16 * ROW_BYTES;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x + 8 * ROW_BYTES));
-                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb[u], oacc[x], 0, 0, 0);
-            }
+        for (int n = 0; n < 4 * DB; ++n) {
+            if (n + PD < 4 * DB) a[n + PD] = v_operand(n + PD);
+            oacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], pb[n / DB], oacc[n % DB], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -526,7 +546,9 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         for (int x = 0; x < DB; ++x)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
-                const int d0 = 32 * x + 8 * e4 + 4 * hh;
+                // O^T row 8*e4 + 4hh + e of block x -> head-dim column (see the V operand mapping)
+                const int m0 = 8 * e4 + 4 * hh;
+                const int d0 = X_COLS * x + (m0 < 16 ? m0 : G16_COLS + m0 - 16);
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][4 * e4 + e] * inv);
@@ -548,14 +570,16 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
     const int gsub = p.group / HP;
     long grid = (pairs >= 8) ? 8L * ((pairs + 7) / 8) * gsub * p.mq : (long)pairs * gsub * p.mq;
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
+    const char *pe = getenv("BSFA_PAD_LDS");
+    const unsigned pad_lds = pe ? (unsigned)atoi(pe) : 0u;
     if (p.counts) {
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), pad_lds, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), pad_lds, stream, p);
     return hipGetLastError();
 }
 
