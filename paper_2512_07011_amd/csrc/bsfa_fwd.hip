@@ -26,7 +26,6 @@
 #include "bsfa_internal.h"
 
 #include <math.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -570,16 +569,14 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
     const int gsub = p.group / HP;
     long grid = (pairs >= 8) ? 8L * ((pairs + 7) / 8) * gsub * p.mq : (long)pairs * gsub * p.mq;
     if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-    const char *pe = getenv("BSFA_PAD_LDS");
-    const unsigned pad_lds = pe ? (unsigned)atoi(pe) : 0u;
     if (p.counts) {
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), pad_lds, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), pad_lds, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -595,9 +592,7 @@ hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool ca
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
     // the copies address a tile with 32-bit element offsets
     if (p.ksn * 64 > 0x7fffffffLL || p.vsn * 64 > 0x7fffffffLL) return hipErrorInvalidValue;
-    const char *ev = getenv("BSFA_VARIANT");
-    const int variant = ev ? atoi(ev) : 0;
-    const bool pair_heads = (p.group % 2 == 0) && variant != 1;
+    const bool pair_heads = (p.group % 2 == 0);
 #define BSFA_CASE(DD, NN, HH, KK) \
     if (head_dim == DD && block_m == 32 * NN) return launch_t<DD, NN, HH, KK>(p, calib, stream);
     if (pair_heads) {
