@@ -191,8 +191,9 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[(KR + VR) * TILE_BYTES];
     __shared__ float lds_red[2][NW];
-    const uint32_t lds_k0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
-    const uint32_t lds_v0 = lds_k0 + KR * TILE_BYTES;
+    // V slots first: their gather offsets then fit the 16-bit immediate of the LDS reads
+    const uint32_t lds_v0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
+    const uint32_t lds_k0 = lds_v0 + VR * TILE_BYTES;
 
     int b, h0, i;
     if (!decode_work<HP>(p, blockIdx.x, b, h0, i)) return;
