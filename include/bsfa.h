@@ -74,6 +74,9 @@ typedef struct {
                              set iff block j was skipped for query tile i */
     float    *block_max;  /* [batch][n_q_heads][M_Q][M_KV]: s_max (Eq. 6, natural score units,
                              1/sqrt(d) included) of gateable blocks, NaN elsewhere */
+    float    *lse;        /* [batch][seqlen][n_q_heads]: L = m + log(l) over the kept blocks, natural
+                             units (last line of Algorithm 1; what a backward pass or a merge of
+                             partial results over key ranges needs) */
 } bsfa_skip_stats;
 
 /*
@@ -108,7 +111,27 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
                            float *thresholds_out, void *workspace, size_t workspace_bytes,
                            void *hip_stream);
 
-/* Bytes of device workspace bsfa_calibrate needs for *p (0 if *p is invalid). */
+/*
+ * Calibration of per-query-tile thresholds, the rule of Section 4.2 itself: for every query head
+ * and query tile, the threshold that retains exactly the top-k gateable key blocks of a
+ * calibration sample (the k-th largest block maximum; -INFINITY where the tile has at most k
+ * gateable blocks, which keeps the min(k, A) of Section 5.1; +INFINITY for k = 0), averaged over
+ * calibration samples.  Each batch element of q, k is one sample.  Calls chain over further
+ * samples: samples_done is the number of samples already averaged into thresholds_out (0 for the
+ * first call, which overwrites it).
+ *   ks             HOST [n_levels], the sparsity levels (number of retained gateable blocks)
+ *   thresholds_out HOST [n_levels][n_q_heads][seqlen / block_m]: one slice [n_q_heads][M_Q] per
+ *                  level, usable as bsfa_forward thresholds with thresholds_per_tile = 1
+ *   workspace      DEVICE, at least bsfa_calibrate_workspace_bytes(p) bytes
+ * p->thresholds_per_tile is ignored.  Synchronises hip_stream.
+ */
+bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                const int32_t *ks, int n_levels, int samples_done,
+                                float *thresholds_out, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
+
+/* Bytes of device workspace bsfa_calibrate and bsfa_calibrate_topk need for *p (0 if *p is
+ * invalid). */
 size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p);
 
 /* Tile shapes and head dims this build supports: fills up to `cap` entries of each array with

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbsfa.so")
 BSFA_OK = 0
 STATUS_NAMES = {0: "BSFA_OK", -1: "BSFA_ERR_NULL", -2: "BSFA_ERR_SHAPE", -3: "BSFA_ERR_DTYPE",
                 -4: "BSFA_ERR_UNSUPPORTED", -5: "BSFA_ERR_WORKSPACE", -6: "BSFA_ERR_HIP"}
-EXPORTS = ["bsfa_forward", "bsfa_calibrate", "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
+EXPORTS = ["bsfa_forward", "bsfa_calibrate", "bsfa_calibrate_topk", "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
            "bsfa_status_string", "bsfa_last_error"]
 
 
@@ -37,7 +37,8 @@ class bsfa_problem(ctypes.Structure):
 
 
 class bsfa_skip_stats(ctypes.Structure):
-    _fields_ = [("counts", ctypes.c_void_p), ("skip_mask", ctypes.c_void_p), ("block_max", ctypes.c_void_p)]
+    _fields_ = [("counts", ctypes.c_void_p), ("skip_mask", ctypes.c_void_p), ("block_max", ctypes.c_void_p),
+                ("lse", ctypes.c_void_p)]
 
 
 _lib = None
@@ -60,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.bsfa_calibrate.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
                                      ctypes.POINTER(ctypes.c_float), ctypes.c_int,
                                      ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
+        L.bsfa_calibrate_topk.restype = ctypes.c_int
+        L.bsfa_calibrate_topk.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_int32), ctypes.c_int, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
         L.bsfa_calibrate_workspace_bytes.restype = ctypes.c_size_t
         L.bsfa_calibrate_workspace_bytes.argtypes = [ctypes.POINTER(bsfa_problem)]
         i32p = ctypes.POINTER(ctypes.c_int32)
@@ -101,9 +106,11 @@ class SkipStats:
     counts: Optional[torch.Tensor] = None      # [B, Hq, 3] int64: skipped, gateable, reachable
     skip_mask: Optional[torch.Tensor] = None   # [B, Hq, M_Q, ceil(M_KV/32)] int32 bit mask
     block_max: Optional[torch.Tensor] = None   # [B, Hq, M_Q, M_KV] fp32, NaN where not gateable
+    lse: Optional[torch.Tensor] = None         # [B, N, Hq] fp32, log-sum-exp over the kept blocks
 
 
-def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_mask=False, block_max=False) -> SkipStats:
+def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_mask=False, block_max=False,
+                lse=False) -> SkipStats:
     B, N, Hq, _ = q.shape
     mq, mkv = N // block_m, N // block_n
     s = SkipStats()
@@ -113,6 +120,8 @@ def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_m
         s.skip_mask = torch.empty(B, Hq, mq, (mkv + 31) // 32, dtype=torch.int32, device=q.device)
     if block_max:
         s.block_max = torch.empty(B, Hq, mq, mkv, dtype=torch.float32, device=q.device)
+    if lse:
+        s.lse = torch.empty(B, N, Hq, dtype=torch.float32, device=q.device)
     return s
 
 
@@ -146,7 +155,8 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
         st = bsfa_skip_stats(
             skip_stats.counts.data_ptr() if skip_stats.counts is not None else None,
             skip_stats.skip_mask.data_ptr() if skip_stats.skip_mask is not None else None,
-            skip_stats.block_max.data_ptr() if skip_stats.block_max is not None else None)
+            skip_stats.block_max.data_ptr() if skip_stats.block_max is not None else None,
+            skip_stats.lse.data_ptr() if skip_stats.lse is not None else None)
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
     _check(lib().bsfa_forward(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), thresholds.data_ptr(),
                               int(bool(causal)), out.data_ptr(), ctypes.byref(st) if st is not None else None,
@@ -176,6 +186,34 @@ def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequ
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 ctypes.c_void_p(s.cuda_stream)))
     return torch.tensor(list(outp), dtype=torch.float32).view(n, q.shape[2])
+
+
+def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m: int = 128, block_n: int = 64,
+                        stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Per-query-tile thresholds for each sparsity level k (number of retained gateable blocks),
+    averaged over the calibration samples: CPU float32 tensor [n_levels, Hq, N/block_m].
+    ``samples`` is a list of (q, k) pairs of equal shape; every batch element is one sample."""
+    n = len(ks)
+    out = None
+    ws = None
+    done = 0
+    kk = (ctypes.c_int32 * n)(*[int(x) for x in ks])
+    for q, k in samples:
+        _dev_check(q, k)
+        if not (q.dtype == k.dtype == torch.bfloat16):
+            raise TypeError("bsfa_calibrate_topk: q, k must be bfloat16")
+        p = make_problem(q, k, None, None, block_m, block_n)
+        need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+        if out is None:
+            out = (ctypes.c_float * (n * q.shape[2] * (q.shape[1] // block_m)))()
+        s = stream if stream is not None else torch.cuda.current_stream(q.device)
+        _check(lib().bsfa_calibrate_topk(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), kk, n, done,
+                                         out, ws.data_ptr(), ws.numel(), ctypes.c_void_p(s.cuda_stream)))
+        done += q.shape[0]
+    q0 = samples[0][0]
+    return torch.tensor(list(out), dtype=torch.float32).view(n, q0.shape[2], q0.shape[1] // block_m)
 
 
 def bsfa_query_build():

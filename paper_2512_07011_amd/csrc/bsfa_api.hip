@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <vector>
 
 namespace {
@@ -94,6 +95,7 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
         fp.counts = reinterpret_cast<unsigned long long *>(skip_stats->counts);
         fp.skip_mask = skip_stats->skip_mask;
         fp.block_max = skip_stats->block_max;
+        fp.lse = skip_stats->lse;
     }
     hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, false, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(BSFA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
@@ -105,6 +107,33 @@ size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
     if (check_problem(p) != BSFA_OK) return 0;
     const size_t mq = (size_t)(p->seqlen / p->block_m), mkv = (size_t)(p->seqlen / p->block_n);
     return (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float) + 256;
+}
+
+// Shared front half of the calibration entry points: checks, score / block-maximum kernel,
+// copy of the [batch][hq][mq][mkv] block maxima (NaN where not gateable) to the host.
+static bsfa_status block_maxima_to_host(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream,
+                                        std::vector<float> &host, bsfa::FwdParams &fp)
+{
+    if (!aligned16(q) || !aligned16(k)) return fail(BSFA_ERR_SHAPE, "q and k must be 16-byte aligned");
+    const size_t need = bsfa_calibrate_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need)
+        return fail(BSFA_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    fill_params(fp, p, causal);
+    fp.q = static_cast<const uint16_t *>(q);
+    fp.k = static_cast<const uint16_t *>(k);
+    fp.block_max = reinterpret_cast<float *>((reinterpret_cast<uintptr_t>(workspace) + 255) & ~(uintptr_t)255);
+    // the score half of the kernel reads a threshold per work item but never acts on it
+    fp.tau = fp.block_max;
+    fp.tau_per_tile = 0;
+    hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
+    host.resize((size_t)p->batch * p->n_q_heads * fp.mq * fp.mkv);
+    e = hipMemcpyAsync(host.data(), fp.block_max, host.size() * sizeof(float), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration copy failed: %s", hipGetErrorString(e));
+    return BSFA_OK;
 }
 
 bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, int causal,
@@ -119,30 +148,13 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
     for (int l = 0; l < n_levels; ++l)
         if (!(target_skip_fractions[l] >= 0.f && target_skip_fractions[l] <= 1.f))
             return fail(BSFA_ERR_SHAPE, "target skip fraction #%d = %g is outside [0, 1]", l, (double)target_skip_fractions[l]);
-    if (!aligned16(q) || !aligned16(k)) return fail(BSFA_ERR_SHAPE, "q and k must be 16-byte aligned");
-    const size_t need = bsfa_calibrate_workspace_bytes(p);
-    if (!workspace || workspace_bytes < need)
-        return fail(BSFA_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
-
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<float> host;
     bsfa::FwdParams fp;
-    fill_params(fp, p, causal);
-    fp.q = static_cast<const uint16_t *>(q);
-    fp.k = static_cast<const uint16_t *>(k);
-    fp.block_max = reinterpret_cast<float *>((reinterpret_cast<uintptr_t>(workspace) + 255) & ~(uintptr_t)255);
-    // the score half of the kernel reads a threshold per work item but never acts on it
-    fp.tau = fp.block_max;
-    fp.tau_per_tile = 0;
-    hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
-    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
+    s = block_maxima_to_host(p, q, k, causal, workspace, workspace_bytes, hip_stream, host, fp);
+    if (s != BSFA_OK) return s;
 
     // selection on the host: per head, order statistic of the gateable block maxima
-    const size_t mq = (size_t)fp.mq, mkv = (size_t)fp.mkv;
-    const size_t per_head = mq * mkv;
-    std::vector<float> host((size_t)p->batch * p->n_q_heads * per_head);
-    e = hipMemcpyAsync(host.data(), fp.block_max, host.size() * sizeof(float), hipMemcpyDeviceToHost, stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(stream);
-    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration copy failed: %s", hipGetErrorString(e));
+    const size_t per_head = (size_t)fp.mq * fp.mkv;
     std::vector<float> vals;
     for (int h = 0; h < p->n_q_heads; ++h) {
         vals.clear();
@@ -163,6 +175,53 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
             }
             thresholds_out[(size_t)l * p->n_q_heads + h] = t;
         }
+    }
+    return BSFA_OK;
+}
+
+bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                const int32_t *ks, int n_levels, int samples_done, float *thresholds_out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    bsfa_status s = check_problem(p);
+    if (s != BSFA_OK) return s;
+    if (!q || !k || !ks || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, ks and thresholds_out must be non-NULL");
+    if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
+    if (samples_done < 0) return fail(BSFA_ERR_SHAPE, "samples_done must be non-negative");
+    for (int l = 0; l < n_levels; ++l)
+        if (ks[l] < 0) return fail(BSFA_ERR_SHAPE, "k #%d = %d is negative", l, ks[l]);
+    std::vector<float> host;
+    bsfa::FwdParams fp;
+    s = block_maxima_to_host(p, q, k, causal, workspace, workspace_bytes, hip_stream, host, fp);
+    if (s != BSFA_OK) return s;
+
+    // per (head, query tile): k-th largest gateable block maximum of each sample (= batch element),
+    // folded into the running mean over samples
+    const size_t mq = (size_t)fp.mq, mkv = (size_t)fp.mkv;
+    std::vector<float> vals;
+    for (int b = 0; b < p->batch; ++b) {
+        const double done = (double)samples_done + b;
+        for (int h = 0; h < p->n_q_heads; ++h)
+            for (size_t i = 0; i < mq; ++i) {
+                const float *src = host.data() + (((size_t)b * p->n_q_heads + h) * mq + i) * mkv;
+                vals.clear();
+                for (size_t x = 0; x < mkv; ++x)
+                    if (!std::isnan(src[x])) vals.push_back(src[x]);
+                const size_t avail = vals.size();
+                for (int l = 0; l < n_levels; ++l) {
+                    const size_t kk = (size_t)ks[l];
+                    float t;
+                    if (avail <= kk) t = -INFINITY;               // keeps min(k, A) = A blocks
+                    else if (kk == 0) t = INFINITY;
+                    else {
+                        std::nth_element(vals.begin(), vals.begin() + (kk - 1), vals.end(), std::greater<float>());
+                        t = vals[kk - 1];
+                    }
+                    float &dst = thresholds_out[((size_t)l * p->n_q_heads + h) * mq + i];
+                    if (done == 0.0 || std::isinf(t)) dst = t;
+                    else dst = (float)(((double)dst * done + (double)t) / (done + 1.0));
+                }
+            }
     }
     return BSFA_OK;
 }

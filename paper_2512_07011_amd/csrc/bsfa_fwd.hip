@@ -541,6 +541,8 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     if constexpr (!CALIB) {
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         const float inv = 1.0f / l_tot;
+        if (p.lse && hh == 0)           // L = m + log(l); m_run is in log2 units
+            p.lse[((int64_t)b * p.seqlen + q_row) * p.hq + h] = m_run * 0.6931471805599453f + __logf(l_tot);
         uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row * p.osn + (int64_t)h * p.osh;
 #pragma unroll
         for (int x = 0; x < DB; ++x)

@@ -20,6 +20,7 @@ struct FwdParams {
     unsigned long long *counts;      // [batch][hq][3] or null
     uint32_t *skip_mask;             // [batch][hq][mq][mask_words] or null
     float *block_max;                // [batch][hq][mq][mkv] or null
+    float *lse;                      // [batch][seqlen][hq] or null
     int mask_words;
 };
 

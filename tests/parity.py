@@ -38,7 +38,7 @@ class ParityReport:
 
 
 def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None, block_max_gpu=None,
-            items=None, oracle_result=None) -> ParityReport:
+            items=None, oracle_result=None, lse_gpu=None) -> ParityReport:
     """q, k, v: the bf16 tensors the kernel saw (any device); tau numpy/torch [Hq] or [Hq, M_Q];
     out_gpu [B,N,Hq,d]; skip_mask_gpu [B,Hq,M_Q,W]; block_max_gpu [B,Hq,M_Q,M_KV]."""
     qf, kf, vf = (t.detach().float().cpu() for t in (q, k, v))
@@ -71,6 +71,10 @@ def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None,
         assert (np.isnan(bg) == np.isnan(r.bmax)).all(), "block_max NaN pattern differs"
         bmax_err = float(np.nanmax(np.abs(bg - r.bmax))) if gate.any() else 0.0
         assert bmax_err <= 1e-4 * max(1.0, float(np.nanmax(np.abs(r.bmax))) if gate.any() else 1.0), "block maxima differ by %g" % bmax_err
+    if lse_gpu is not None:
+        lg = lse_gpu.detach().cpu().numpy().reshape(B, mq, block_m, Hq)[ib, ii, :, ih]   # [n, BM]
+        lse_err = float(np.abs(lg - ref.lse).max())
+        assert lse_err <= 5e-3, "log-sum-exp differs by %g" % lse_err
     og = out_gpu.detach().float().cpu().numpy()
     og = og.reshape(B, mq, block_m, Hq, d)[ib, ii, :, ih]                                # [n, BM, d]
     assert np.isfinite(og).all(), "non-finite output"

@@ -86,6 +86,20 @@ def test_calibrate_argument_checks(lib):
     assert lib.bsfa_calibrate(ctypes.byref(pt), FAKE, FAKE, 1, fr, 2, out, FAKE, need, None) == -4
 
 
+def test_calibrate_topk_argument_checks(lib):
+    p = good_problem()
+    need = lib.bsfa_calibrate_workspace_bytes(ctypes.byref(p))
+    ks = (ctypes.c_int32 * 2)(4, 8)
+    out = (ctypes.c_float * (2 * 4 * 4))()
+    assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, ks, 2, 0, out, None, 0, None) == -5
+    assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, None, 2, 0, out, FAKE, need, None) == -1
+    assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, ks, 0, 0, out, FAKE, need, None) == -2
+    assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, ks, 2, -1, out, FAKE, need, None) == -2
+    neg = (ctypes.c_int32 * 1)(-3)
+    assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, neg, 1, 0, out, FAKE, need, None) == -2
+    assert lib.bsfa_calibrate_topk(ctypes.byref(good_problem(seqlen=500)), FAKE, FAKE, 1, ks, 2, 0, out, FAKE, need, None) == -2
+
+
 def test_query_build_and_status_strings(lib):
     tiles = binding.bsfa_query_build()
     assert (128, 64, 128) in tiles and (64, 64, 64) in tiles

@@ -12,7 +12,7 @@ DEV = "cuda"
 
 
 def run_gpu(q, k, v, tau, bm, bn, causal=True, dump=True):
-    st = binding.alloc_stats(q, bm, bn, counts=True, skip_mask=True, block_max=dump)
+    st = binding.alloc_stats(q, bm, bn, counts=True, skip_mask=True, block_max=dump, lse=dump)
     out = binding.bsfa_forward(q, k, v, tau, causal=causal, skip_stats=st, block_m=bm, block_n=bn)
     torch.cuda.synchronize()
     return out, st
@@ -28,7 +28,7 @@ def full_case(shp, q, k, v, fraction, causal=True, oracle=None):
     qd, kd, vd = to_dev(q, k, v)
     neg = torch.full((shp.n_q_heads,), float("-inf"), device=DEV)
     out, st = run_gpu(qd, kd, vd, neg, shp.block_m, shp.block_n, causal)
-    rep = parity.compare(qd, kd, vd, neg, shp.block_m, shp.block_n, causal, out, st.skip_mask, st.block_max)
+    rep = parity.compare(qd, kd, vd, neg, shp.block_m, shp.block_n, causal, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
     assert rep.skipped == 0 and rep.mask_mismatch == 0
     assert (st.counts[..., 0] == 0).all()
     # thresholds at the requested quantile of the oracle's block maxima
@@ -38,7 +38,7 @@ def full_case(shp, q, k, v, fraction, causal=True, oracle=None):
     tau = oracle.calibrate(dense.bmax, dense.cls, [fraction])[0]
     taud = torch.from_numpy(tau).to(DEV)
     out, st = run_gpu(qd, kd, vd, taud, shp.block_m, shp.block_n, causal)
-    rep = parity.compare(qd, kd, vd, tau, shp.block_m, shp.block_n, causal, out, st.skip_mask, st.block_max)
+    rep = parity.compare(qd, kd, vd, tau, shp.block_m, shp.block_n, causal, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
     assert rep.skipped > 0
     c = st.counts.cpu().numpy()
     m = parity.unpack_mask(st.skip_mask.cpu().numpy(), shp.m_kv)
@@ -164,3 +164,36 @@ def test_gqa_degeneracy_on_gpu():
     for h in range(1, 4):
         assert torch.equal(out[:, :, h], out[:, :, 0])
         assert torch.equal(st.skip_mask[:, h], st.skip_mask[:, 0])
+
+
+def test_calibrate_topk_matches_section_4_2_rule(oracle):
+    """bsfa_calibrate_topk against the oracle's per-tile top-k rule applied to the kernel's own
+    block-maximum dump (two calibration samples, three sparsity levels), then the thresholds in use:
+    on a calibration sample every tile keeps min(k, A) gateable blocks up to in-band flips and the
+    measured density equals the closed form of the paper's Metrics paragraph."""
+    shp = synth.Shape(1, 2048, 4, 2, 128, 128, 64)
+    samples = [to_dev(*synth.llama_layer(s, shp)) for s in (31, 32)]
+    ks = [2, 8, 20]
+    T = binding.bsfa_calibrate_topk([(q, k) for q, k, _ in samples], ks)          # [levels, Hq, MQ]
+    gate = oracle.gateable_mask(2048, 128, 64)
+    neg = torch.full((4,), float("-inf"), device=DEV)
+    dumps = []
+    for q, k, v in samples:
+        _, st = run_gpu(q, k, v, neg, 128, 64)
+        dumps.append(st.block_max.cpu().numpy()[0])
+    ref = oracle.calibrate_topk(dumps, gate, ks)
+    assert (np.isinf(ref) == np.isinf(T.numpy())).all()
+    fin = np.isfinite(ref)
+    assert np.abs(ref[fin] - T.numpy()[fin]).max() <= 1e-6 * np.abs(ref[fin]).max()
+    # single-sample thresholds are exact order statistics of that sample
+    T0 = binding.bsfa_calibrate_topk([samples[0][:2]], ks)
+    assert (T0.numpy() == oracle.calibrate_topk(dumps[:1], gate, ks)).all()
+    q, k, v = samples[0]
+    for li, kk in enumerate(ks):
+        out, st = run_gpu(q, k, v, T0[li].contiguous().to(DEV), 128, 64)
+        rep = parity.compare(q, k, v, T0[li].numpy(), 128, 64, True, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
+        kept = (~parity.unpack_mask(st.skip_mask.cpu().numpy(), shp.m_kv)) & gate[None, None]
+        assert np.abs(kept.sum(-1) - np.minimum(kk, gate.sum(1))[None, None]).sum() <= rep.mask_mismatch
+        c = st.counts.cpu().numpy()
+        dens = 1 - c[..., 0].sum() / c[..., 2].sum()
+        assert abs(dens - oracle.predicted_density(2048, 128, 64, kk)) <= (rep.mask_mismatch + 0.5) / c[..., 2].sum()
