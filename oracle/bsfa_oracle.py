@@ -90,40 +90,82 @@ class ItemResult:
     lse: np.ndarray        # [n][BM] fp32
 
 
+def _pad_last_token(x: np.ndarray, n_pad: int) -> np.ndarray:
+    """Section 4.3: a sequence that does not fill its last block is padded by repeating its
+    last token."""
+    N = x.shape[1]
+    if n_pad == N:
+        return x
+    return np.ascontiguousarray(np.concatenate([x, np.repeat(x[:, N - 1:N], n_pad - N, axis=1)], axis=1))
+
+
+def _expand_tau(tau, Hq, mq_pad):
+    """Thresholds as the C oracle wants them.  Per-tile thresholds [Hq, T] with fewer tiles than
+    the sequence has are extended with their last column: positions beyond the calibrated
+    length reuse the thresholds of the last calibrated position (Section 4.3)."""
+    tau = np.asarray(tau, dtype=np.float32)
+    if tau.ndim == 1:
+        assert tau.shape == (Hq,)
+        return np.ascontiguousarray(tau), 0
+    assert tau.ndim == 2 and tau.shape[0] == Hq and tau.shape[1] >= 1
+    T = tau.shape[1]
+    if T < mq_pad:
+        tau = np.concatenate([tau, np.repeat(tau[:, T - 1:T], mq_pad - T, axis=1)], axis=1)
+    return np.ascontiguousarray(tau[:, :mq_pad]), 1
+
+
 def forward_items(q, k, v, tau, block_m, block_n, causal=True, items=None, forced_keep=None) -> ItemResult:
     """Evaluate the oracle on a list of (b, h, i) query tiles (all of them if ``items`` is None).
 
-    q [B,N,Hq,d], k/v [B,N,Hkv,d]; tau [Hq] or [Hq, N/block_m]; forced_keep optional
-    [n_items, N/block_n] overriding the gate on gateable blocks."""
+    q [B,N,Hq,d], k/v [B,N,Hkv,d]; tau [Hq] or [Hq, T] (T < M_Q: the last column serves every
+    later tile); forced_keep optional [n_items, M_KV] overriding the gate on gateable blocks.
+    M_Q = ceil(N / block_m), M_KV = ceil(N / block_n).  If N does not fill its last block
+    (causal only) the inputs are padded by repeating the last token (Section 4.3), the padded
+    problem is evaluated, and everything that belongs to padded rows or to key blocks made
+    of padding only is dropped: rows >= N of the last tile come back as NaN."""
     q, k, v = _f32(q), _f32(k), _f32(v)
     B, N, Hq, d = q.shape
     Hkv = k.shape[2]
     assert k.shape == (B, N, Hkv, d) and v.shape == k.shape
-    MQ, MKV = N // block_m, N // block_n
-    tau = np.ascontiguousarray(np.asarray(tau, dtype=np.float32))
-    per_tile = int(tau.ndim == 2)
-    assert tau.shape == ((Hq, MQ) if per_tile else (Hq,))
+    MQ, MKV = -(-N // block_m), -(-N // block_n)
+    big = max(block_m, block_n)
+    assert big % block_m == 0 and big % block_n == 0
+    n_pad = -(-N // big) * big
+    if n_pad != N:
+        assert causal, "padding by repetition is defined for the causal case only"
+        q, k, v = (_pad_last_token(x, n_pad) for x in (q, k, v))
+    mq_pad, mkv_pad = n_pad // block_m, n_pad // block_n
+    tau, per_tile = _expand_tau(tau, Hq, mq_pad)
     if items is None:
         items = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(MQ)]
     items = np.ascontiguousarray(np.asarray(items, dtype=np.int32).reshape(-1, 3))
+    assert items[:, 2].max(initial=0) < MQ
     n = items.shape[0]
     fk = None
     if forced_keep is not None:
-        fk = np.ascontiguousarray(np.asarray(forced_keep, dtype=np.uint8))
+        fk = np.asarray(forced_keep, dtype=np.uint8)
         assert fk.shape == (n, MKV)
+        fk = np.ascontiguousarray(np.pad(fk, ((0, 0), (0, mkv_pad - MKV)), constant_values=1))
     out = np.empty((n, block_m, d), np.float32)
-    bmax = np.empty((n, MKV), np.float32)
-    cls = np.empty((n, MKV), np.uint8)
+    bmax = np.empty((n, mkv_pad), np.float32)
+    cls = np.empty((n, mkv_pad), np.uint8)
     psum = np.empty((n, block_m), np.float64)
     lse = np.empty((n, block_m), np.float32)
     rc = _load().bsfa_oracle_items(
         _ptr(q, ctypes.c_float), _ptr(k, ctypes.c_float), _ptr(v, ctypes.c_float),
-        B, N, Hq, Hkv, d, block_m, block_n, int(bool(causal)),
+        B, n_pad, Hq, Hkv, d, block_m, block_n, int(bool(causal)),
         _ptr(tau, ctypes.c_float), per_tile, _ptr(items, ctypes.c_int32), n,
         _ptr(fk, ctypes.c_uint8), _ptr(out, ctypes.c_float), _ptr(bmax, ctypes.c_float),
         _ptr(cls, ctypes.c_uint8), _ptr(psum, ctypes.c_double), _ptr(lse, ctypes.c_float))
     if rc != 0:
         raise RuntimeError("bsfa_oracle_items failed with code %d" % rc)
+    if n_pad != N:
+        pad_rows = (items[:, 2:3] * block_m + np.arange(block_m)[None, :]) >= N     # [n, BM]
+        out[pad_rows] = np.nan
+        psum[pad_rows] = np.nan
+        lse[pad_rows] = np.nan
+        bmax = np.ascontiguousarray(bmax[:, :MKV])
+        cls = np.ascontiguousarray(cls[:, :MKV])
     return ItemResult(items, out, bmax, cls, psum, lse)
 
 
@@ -139,14 +181,14 @@ class FullResult:
 
 def forward(q, k, v, tau, block_m, block_n, causal=True, forced_keep=None) -> FullResult:
     """Oracle on the whole problem, results re-assembled into tensor layout.
-    ``forced_keep`` optional [B,Hq,M_Q,M_KV]."""
+    ``forced_keep`` optional [B,Hq,M_Q,M_KV]; M_Q, M_KV rounded up for ragged N."""
     B, N, Hq, d = q.shape
-    MQ, MKV = N // block_m, N // block_n
+    MQ, MKV = -(-N // block_m), -(-N // block_n)
     fk = None if forced_keep is None else np.asarray(forced_keep).reshape(B * Hq * MQ, MKV)
     r = forward_items(q, k, v, tau, block_m, block_n, causal, None, fk)
-    out = r.out.reshape(B, Hq, MQ, block_m, d).transpose(0, 2, 3, 1, 4).reshape(B, N, Hq, d)
-    psum = r.psum.reshape(B, Hq, MQ, block_m).transpose(0, 2, 3, 1).reshape(B, N, Hq)
-    lse = r.lse.reshape(B, Hq, MQ, block_m).transpose(0, 2, 3, 1).reshape(B, N, Hq)
+    out = r.out.reshape(B, Hq, MQ, block_m, d).transpose(0, 2, 3, 1, 4).reshape(B, MQ * block_m, Hq, d)[:, :N]
+    psum = r.psum.reshape(B, Hq, MQ, block_m).transpose(0, 2, 3, 1).reshape(B, MQ * block_m, Hq)[:, :N]
+    lse = r.lse.reshape(B, Hq, MQ, block_m).transpose(0, 2, 3, 1).reshape(B, MQ * block_m, Hq)[:, :N]
     cls = r.cls.reshape(B, Hq, MQ, MKV)
     return FullResult(np.ascontiguousarray(out), r.bmax.reshape(B, Hq, MQ, MKV), cls,
                       np.ascontiguousarray(psum), np.ascontiguousarray(lse), counts_from_cls(cls))
@@ -266,7 +308,7 @@ def calibrate_topk(bmax_samples, gateable, ks) -> np.ndarray:
 
 def gateable_mask(seqlen, block_m, block_n, causal=True) -> np.ndarray:
     """[M_Q, M_KV] bool: blocks the gate applies to (fully visible, not overlapping the tile)."""
-    MQ, MKV = seqlen // block_m, seqlen // block_n
+    MQ, MKV = -(-seqlen // block_m), -(-seqlen // block_n)
     i = np.arange(MQ)[:, None]
     j = np.arange(MKV)[None, :]
     if causal:

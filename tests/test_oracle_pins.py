@@ -317,3 +317,87 @@ def test_items_subset_matches_full(oracle):
     for n, (b, h, i) in enumerate(items):
         assert (r.out[n] == full.out[b, i * 128:(i + 1) * 128, h]).all()
         assert (r.cls[n] == full.cls[b, h, i]).all()
+
+
+# ---- sequences that do not fill their last block, thresholds shorter than the sequence -------
+RAGGED = [
+    # (B, N_aligned, Hq, Hkv, d, BM, BN), N
+    ((1, 512, 2, 2, 64, 64, 64), 450),       # partial last tile and block
+    ((2, 512, 4, 2, 32, 128, 64), 322),      # last tile covers 66 of 128 rows, 3 blocks of which one partial
+    ((1, 384, 4, 1, 16, 128, 64), 260),      # last tile's second boundary block is padding only
+    ((1, 256, 4, 2, 16, 32, 64), 197),       # B_M < B_N
+    ((1, 128, 2, 1, 16, 128, 64), 1),        # a single token
+]
+
+
+def ragged_reference(q, k, v, tau_tiles, bm, bn):
+    """What Section 4.3's padding rule must amount to, from the real N x N matrix only: block
+    maxima over the rows and columns that exist, the gate on blocks that lie entirely before
+    the tile's first row, masked softmax over kept entries.  tau_tiles [Hq, MQ]."""
+    B, N, Hq, d = q.shape
+    MQ, MKV = -(-N // bm), -(-N // bn)
+    S = brute_scores(q, k)
+    keep = np.ones((B, Hq, N, N), bool)
+    bmax = np.full((B, Hq, MQ, MKV), np.nan)
+    skipped = np.zeros((B, Hq, MQ, MKV), bool)
+    for i in range(MQ):
+        r0, r1 = i * bm, min((i + 1) * bm, N)
+        for j in range(MKV):
+            c0, c1 = j * bn, min((j + 1) * bn, N)
+            if (j + 1) * bn - 1 <= r0:                        # gateable: whole block visible to every row
+                assert c1 == (j + 1) * bn
+                m = S[:, :, r0:r1, c0:c1].max(axis=(2, 3))    # [B,Hq]
+                bmax[:, :, i, j] = m
+                sk = m.astype(np.float32) < tau_tiles[None, :, i]
+                skipped[:, :, i, j] = sk
+                keep[:, :, r0:r1, c0:c1] = ~sk[:, :, None, None]
+    out, _ = brute_attention(q, k, v, key_keep=keep)
+    return out, bmax, skipped
+
+
+@pytest.mark.parametrize("case,N", RAGGED)
+def test_p11_ragged_padding_equals_ignoring_out_of_range(oracle, case, N):
+    shp, q, k, v = make(case, seed=31)
+    q, k, v = (np.ascontiguousarray(x[:, :N]) for x in (q, k, v))
+    bm, bn, Hq = shp.block_m, shp.block_n, shp.n_q_heads
+    MQ, MKV = -(-N // bm), -(-N // bn)
+    dense = oracle.forward(q, k, v, np.full(Hq, -np.inf, np.float32), bm, bn)
+    assert dense.out.shape == q.shape and dense.bmax.shape == (shp.batch, Hq, MQ, MKV)
+    ref, bmax_ref, _ = ragged_reference(q, k, v, np.full((Hq, MQ), -np.inf, np.float32), bm, bn)
+    assert np.abs(dense.out - ref).max() < 2e-6
+    gate = ~np.isnan(bmax_ref)
+    assert (gate == np.broadcast_to(oracle.gateable_mask(N, bm, bn), gate.shape)).all()
+    assert (np.isnan(dense.bmax) == ~gate).all()
+    np.testing.assert_allclose(dense.bmax[gate], bmax_ref[gate], rtol=0, atol=1e-6)
+    i = np.arange(MQ)[:, None]
+    j = np.arange(MKV)[None, :]
+    reach = j * bn <= np.minimum((i + 1) * bm, N) - 1
+    assert ((dense.cls != oracle.CLS_UNREACHABLE) == reach[None, None]).all()
+    if gate.any():
+        # per-tile thresholds at the median of each head's maxima, shifted per tile
+        med = np.array([np.median(dense.bmax[:, h][gate[:, h]]) for h in range(Hq)], np.float32)
+        tau = (med[:, None] + 0.05 * np.arange(MQ)[None, :]).astype(np.float32)
+        r = oracle.forward(q, k, v, tau, bm, bn)
+        ref, _, skipped = ragged_reference(q, k, v, tau, bm, bn)
+        assert ((r.cls == oracle.CLS_SKIPPED) == skipped).all()
+        assert 0 < skipped.sum() < gate.sum()
+        assert np.abs(r.out - ref).max() < 2e-6
+        assert (r.counts[..., 0] == skipped.sum(axis=(2, 3))).all()
+        assert (r.counts[..., 2] == reach.sum()).all()
+
+
+def test_p12_thresholds_beyond_calibrated_length_reuse_last(oracle):
+    """Section 4.3: positions past the calibrated length take the last calibrated thresholds."""
+    shp, q, k, v = make(CASES[0], seed=37)
+    bm, bn, Hq = shp.block_m, shp.block_n, shp.n_q_heads
+    dense = oracle.forward(q, k, v, np.full(Hq, -np.inf, np.float32), bm, bn)
+    gate = oracle.gateable_mask(shp.seqlen, bm, bn)
+    T = 3
+    rng = np.random.default_rng(5)
+    short = (np.nanmedian(dense.bmax[0], axis=(1, 2))[:, None] + rng.normal(0, 0.3, (Hq, T))).astype(np.float32)
+    r = oracle.forward(q, k, v, short, bm, bn)
+    used = short[:, np.minimum(np.arange(shp.m_q), T - 1)]               # [Hq, MQ]
+    expect = gate[None, None] & (dense.bmax < used[None, :, :, None])
+    assert ((r.cls == oracle.CLS_SKIPPED) == expect).all() and expect.any()
+    ref, _, _ = ragged_reference(q, k, v, used, bm, bn)
+    assert np.abs(r.out - ref).max() < 2e-6
