@@ -11,6 +11,12 @@
  * last paragraph).  Equality keeps the block (Section 4.1 states the skip condition as a
  * strict inequality).
  *
+ * Sequence lengths.  M_Q = ceil(seqlen / block_m) query tiles and M_KV = ceil(seqlen / block_n)
+ * key blocks.  With causal != 0 seqlen need not fill its last tile or block: the sequence then
+ * behaves as if padded by repeating its last token (Section 4.3).  Because of the causal mask that
+ * amounts to ignoring the rows and columns that do not exist; the library never reads or writes
+ * a token index >= seqlen.  With causal == 0 seqlen must be a multiple of block_m and block_n.
+ *
  * Conventions
  *  - Every data pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all
  *    buffers; the library keeps no device memory between calls.
@@ -48,7 +54,8 @@ typedef enum {
 typedef enum { BSFA_BF16 = 0 } bsfa_dtype; /* inputs/outputs bf16, fp32 accumulation */
 
 /* Problem descriptor (paper notation, Section 2.2: N tokens, head dim d, query tiles of B_M
- * rows, key/value blocks of B_N rows).  seqlen must be a multiple of block_m and block_n. */
+ * rows, key/value blocks of B_N rows).  Zero-initialise it: a zero in an optional member selects
+ * its default. */
 typedef struct {
     int32_t batch, n_q_heads, n_kv_heads, seqlen, head_dim;
     int32_t block_m, block_n;     /* gate tile; see bsfa_query_build for the supported shapes */
@@ -58,9 +65,21 @@ typedef struct {
     int64_t o_stride_b, o_stride_n, o_stride_h;
     int32_t dtype;                /* bsfa_dtype */
     int32_t thresholds_per_tile;  /* 0: thresholds[n_q_heads] (one per head);
-                                     1: thresholds[n_q_heads][seqlen/block_m], the paper's
+                                     1: thresholds[n_q_heads][threshold_tiles], the paper's
                                         T_{l,h,i} for one layer and one sparsity level
                                         (Section 4.2) */
+    int32_t threshold_tiles;      /* optional, thresholds_per_tile = 1 only: number of query tiles
+                                     the thresholds were calibrated for (row length of the array);
+                                     0 = M_Q.  Query tiles at and beyond it use the last
+                                     calibrated tile's threshold, the rule of Section 4.3 for
+                                     sequences longer than the calibration length. */
+    const int32_t *seqlens;       /* optional, DEVICE [batch], causal only: tokens of each batch
+                                     element, clamped to [0, seqlen]; NULL = all have seqlen.
+                                     Element b is handled as a sequence of seqlens[b] tokens stored
+                                     at the start of its [seqlen] slot: rows of out and lse at and
+                                     beyond seqlens[b] are left untouched, query tiles beyond it
+                                     get NaN block maxima, an empty skip mask and add nothing to
+                                     counts. */
 } bsfa_problem;
 
 /* Optional outputs of bsfa_forward; any member may be NULL.  All DEVICE, caller allocated.
@@ -120,10 +139,12 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
  * samples: samples_done is the number of samples already averaged into thresholds_out (0 for the
  * first call, which overwrites it).
  *   ks             HOST [n_levels], the sparsity levels (number of retained gateable blocks)
- *   thresholds_out HOST [n_levels][n_q_heads][seqlen / block_m]: one slice [n_q_heads][M_Q] per
- *                  level, usable as bsfa_forward thresholds with thresholds_per_tile = 1
+ *   thresholds_out HOST [n_levels][n_q_heads][M_Q]: one slice [n_q_heads][M_Q] per level, usable
+ *                  as bsfa_forward thresholds with thresholds_per_tile = 1 (and, on a longer
+ *                  sequence, with threshold_tiles = this M_Q)
  *   workspace      DEVICE, at least bsfa_calibrate_workspace_bytes(p) bytes
- * p->thresholds_per_tile is ignored.  Synchronises hip_stream.
+ * p->thresholds_per_tile and p->threshold_tiles are ignored; p->seqlens must be NULL (samples of
+ * one call have one length).  Synchronises hip_stream.
  */
 bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,
                                 const int32_t *ks, int n_levels, int samples_done,

@@ -33,7 +33,8 @@ class bsfa_problem(ctypes.Structure):
                [(n, ctypes.c_int64) for n in
                 ("q_stride_b", "q_stride_n", "q_stride_h", "k_stride_b", "k_stride_n", "k_stride_h",
                  "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
-               [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32)]
+               [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32),
+                ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p)]
 
 
 class bsfa_skip_stats(ctypes.Structure):
@@ -84,7 +85,8 @@ def _check(status: int):
 
 
 def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], out: Optional[torch.Tensor],
-                 block_m: int, block_n: int, thresholds_per_tile: bool = False) -> bsfa_problem:
+                 block_m: int, block_n: int, thresholds_per_tile: bool = False, threshold_tiles: int = 0,
+                 seqlens: Optional[torch.Tensor] = None) -> bsfa_problem:
     """Descriptor for [B, N, H, d] views (any strides with a contiguous last dimension)."""
     B, N, Hq, d = q.shape
     p = bsfa_problem()
@@ -98,7 +100,17 @@ def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], ou
         setattr(p, name + "_stride_h", t.stride(2))
     p.dtype = 0
     p.thresholds_per_tile = int(thresholds_per_tile)
+    p.threshold_tiles = int(threshold_tiles)
+    if seqlens is not None:
+        if seqlens.dtype != torch.int32 or not seqlens.is_contiguous() or tuple(seqlens.shape) != (B,) or not seqlens.is_cuda:
+            raise TypeError("bsfa: seqlens must be a contiguous int32 GPU tensor of shape [batch]")
+        p.seqlens = seqlens.data_ptr()
     return p
+
+
+def n_tiles(n: int, block: int) -> int:
+    """Query tiles / key blocks of a sequence of n tokens (the last one may be partial)."""
+    return -(-n // block)
 
 
 @dataclass
@@ -112,7 +124,7 @@ class SkipStats:
 def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_mask=False, block_max=False,
                 lse=False) -> SkipStats:
     B, N, Hq, _ = q.shape
-    mq, mkv = N // block_m, N // block_n
+    mq, mkv = n_tiles(N, block_m), n_tiles(N, block_n)
     s = SkipStats()
     if counts:
         s.counts = torch.empty(B, Hq, 3, dtype=torch.int64, device=q.device)
@@ -134,9 +146,12 @@ def _dev_check(*ts):
 def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: torch.Tensor,
                  causal: bool = True, out: Optional[torch.Tensor] = None,
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
-                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                 stream: Optional[torch.cuda.Stream] = None,
+                 seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
     """out = block-sparse attention of bf16 q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
-    GPU, [Hq] or [Hq, N/block_m].  Enqueues on ``stream`` (default: torch's current stream)."""
+    GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
+    GPU tensor [B], causal only) gives each batch element its own length.  Enqueues on
+    ``stream`` (default: torch's current stream)."""
     _dev_check(q, k, v, thresholds, out)
     if not (q.dtype == k.dtype == v.dtype == torch.bfloat16):
         raise TypeError("bsfa_forward: q, k, v must be bfloat16")
@@ -144,12 +159,11 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
         raise TypeError("bsfa_forward: thresholds must be contiguous float32")
     per_tile = thresholds.dim() == 2
     B, N, Hq, d = q.shape
-    want = (Hq, N // block_m) if per_tile else (Hq,)
-    if tuple(thresholds.shape) != want:
-        raise ValueError("bsfa_forward: thresholds shape %s, expected %s" % (tuple(thresholds.shape), want))
+    if thresholds.dim() not in (1, 2) or thresholds.shape[0] != Hq or (per_tile and thresholds.shape[1] < 1):
+        raise ValueError("bsfa_forward: thresholds shape %s, expected [Hq] or [Hq, tiles]" % (tuple(thresholds.shape),))
     if out is None:
         out = torch.empty_like(q)
-    p = make_problem(q, k, v, out, block_m, block_n, per_tile)
+    p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens)
     st = None
     if skip_stats is not None:
         st = bsfa_skip_stats(
@@ -167,12 +181,13 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
 def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequence[float],
                    causal: bool = True, block_m: int = 128, block_n: int = 64,
                    workspace: Optional[torch.Tensor] = None,
-                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                   stream: Optional[torch.cuda.Stream] = None,
+                   seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Per-head thresholds for each target skip fraction: CPU float32 tensor [n_levels, Hq]."""
     _dev_check(q, k, workspace)
     if not (q.dtype == k.dtype == torch.bfloat16):
         raise TypeError("bsfa_calibrate: q, k must be bfloat16")
-    p = make_problem(q, k, None, None, block_m, block_n)
+    p = make_problem(q, k, None, None, block_m, block_n, seqlens=seqlens)
     need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
     if need == 0:
         _check(lib().bsfa_calibrate(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), None, 0, None, None, 0, None))
@@ -191,7 +206,7 @@ def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequ
 def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m: int = 128, block_n: int = 64,
                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
     """Per-query-tile thresholds for each sparsity level k (number of retained gateable blocks),
-    averaged over the calibration samples: CPU float32 tensor [n_levels, Hq, N/block_m].
+    averaged over the calibration samples: CPU float32 tensor [n_levels, Hq, ceil(N/block_m)].
     ``samples`` is a list of (q, k) pairs of equal shape; every batch element is one sample."""
     n = len(ks)
     out = None
@@ -207,13 +222,13 @@ def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m
         if ws is None or ws.numel() < need:
             ws = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
         if out is None:
-            out = (ctypes.c_float * (n * q.shape[2] * (q.shape[1] // block_m)))()
+            out = (ctypes.c_float * (n * q.shape[2] * n_tiles(q.shape[1], block_m)))()
         s = stream if stream is not None else torch.cuda.current_stream(q.device)
         _check(lib().bsfa_calibrate_topk(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), kk, n, done,
                                          out, ws.data_ptr(), ws.numel(), ctypes.c_void_p(s.cuda_stream)))
         done += q.shape[0]
     q0 = samples[0][0]
-    return torch.tensor(list(out), dtype=torch.float32).view(n, q0.shape[2], q0.shape[1] // block_m)
+    return torch.tensor(list(out), dtype=torch.float32).view(n, q0.shape[2], n_tiles(q0.shape[1], block_m))
 
 
 def bsfa_query_build():

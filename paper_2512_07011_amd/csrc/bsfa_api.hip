@@ -25,7 +25,7 @@ bsfa_status fail(bsfa_status s, const char *fmt, ...)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bsfa_status check_problem(const bsfa_problem *p)
+bsfa_status check_problem(const bsfa_problem *p, int causal)
 {
     if (!p) return fail(BSFA_ERR_NULL, "problem descriptor is NULL");
     if (p->dtype != BSFA_BF16) return fail(BSFA_ERR_DTYPE, "dtype %d not supported (bf16 only)", p->dtype);
@@ -38,9 +38,11 @@ bsfa_status check_problem(const bsfa_problem *p)
     if (!bsfa::shape_supported(p->head_dim, p->block_m, p->block_n))
         return fail(BSFA_ERR_UNSUPPORTED, "head_dim %d with tile %dx%d is not built (see bsfa_query_build)",
                     p->head_dim, p->block_m, p->block_n);
-    if (p->seqlen % p->block_m || p->seqlen % p->block_n)
-        return fail(BSFA_ERR_SHAPE, "seqlen %d is not a multiple of block_m %d and block_n %d", p->seqlen,
-                    p->block_m, p->block_n);
+    if (!causal && (p->seqlen % p->block_m || p->seqlen % p->block_n))
+        return fail(BSFA_ERR_SHAPE, "seqlen %d is not a multiple of block_m %d and block_n %d (required without the causal mask)",
+                    p->seqlen, p->block_m, p->block_n);
+    if (!causal && p->seqlens) return fail(BSFA_ERR_SHAPE, "per-element sequence lengths need the causal mask");
+    if (p->seqlens && (reinterpret_cast<uintptr_t>(p->seqlens) & 3u)) return fail(BSFA_ERR_SHAPE, "seqlens must be 4-byte aligned");
     const int64_t st[12] = {p->q_stride_b, p->q_stride_n, p->q_stride_h, p->k_stride_b, p->k_stride_n, p->k_stride_h,
                             p->v_stride_b, p->v_stride_n, p->v_stride_h, p->o_stride_b, p->o_stride_n, p->o_stride_h};
     for (int x = 0; x < 12; ++x) {
@@ -49,6 +51,7 @@ bsfa_status check_problem(const bsfa_problem *p)
     }
     if (p->thresholds_per_tile != 0 && p->thresholds_per_tile != 1)
         return fail(BSFA_ERR_SHAPE, "thresholds_per_tile must be 0 or 1");
+    if (p->threshold_tiles < 0) return fail(BSFA_ERR_SHAPE, "threshold_tiles must not be negative");
     return BSFA_OK;
 }
 
@@ -62,8 +65,10 @@ void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
     fp.batch = p->batch; fp.hq = p->n_q_heads; fp.hkv = p->n_kv_heads;
     fp.group = p->n_q_heads / p->n_kv_heads;
     fp.seqlen = p->seqlen;
-    fp.mq = p->seqlen / p->block_m;
-    fp.mkv = p->seqlen / p->block_n;
+    fp.mq = (p->seqlen + p->block_m - 1) / p->block_m;
+    fp.mkv = (p->seqlen + p->block_n - 1) / p->block_n;
+    fp.seqlens = p->seqlens;
+    fp.tau_tiles = p->threshold_tiles > 0 ? p->threshold_tiles : fp.mq;
     fp.mask_words = (fp.mkv + 31) / 32;
     fp.causal = causal ? 1 : 0;
     fp.tau_per_tile = p->thresholds_per_tile;
@@ -79,7 +84,7 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
                          const float *thresholds, int causal, void *out,
                          const bsfa_skip_stats *skip_stats, void *hip_stream)
 {
-    bsfa_status s = check_problem(p);
+    bsfa_status s = check_problem(p, causal);
     if (s != BSFA_OK) return s;
     if (!q || !k || !v || !thresholds || !out) return fail(BSFA_ERR_NULL, "q, k, v, thresholds and out must be non-NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
@@ -104,8 +109,8 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
 
 size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
 {
-    if (check_problem(p) != BSFA_OK) return 0;
-    const size_t mq = (size_t)(p->seqlen / p->block_m), mkv = (size_t)(p->seqlen / p->block_n);
+    if (check_problem(p, 1) != BSFA_OK) return 0;
+    const size_t mq = (size_t)((p->seqlen + p->block_m - 1) / p->block_m), mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
     return (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float) + 256;
 }
 
@@ -127,6 +132,7 @@ static bsfa_status block_maxima_to_host(const bsfa_problem *p, const void *q, co
     // the score half of the kernel reads a threshold per work item but never acts on it
     fp.tau = fp.block_max;
     fp.tau_per_tile = 0;
+    fp.tau_tiles = 1;
     hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
     if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
     host.resize((size_t)p->batch * p->n_q_heads * fp.mq * fp.mkv);
@@ -140,7 +146,7 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
                            const float *target_skip_fractions, int n_levels, float *thresholds_out,
                            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    bsfa_status s = check_problem(p);
+    bsfa_status s = check_problem(p, causal);
     if (s != BSFA_OK) return s;
     if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate produces per-head thresholds only");
     if (!q || !k || !target_skip_fractions || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, fractions and thresholds_out must be non-NULL");
@@ -183,8 +189,9 @@ bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void
                                 const int32_t *ks, int n_levels, int samples_done, float *thresholds_out,
                                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    bsfa_status s = check_problem(p);
+    bsfa_status s = check_problem(p, causal);
     if (s != BSFA_OK) return s;
+    if (p->seqlens) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate_topk takes samples of one length (seqlens must be NULL)");
     if (!q || !k || !ks || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, ks and thresholds_out must be non-NULL");
     if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
     if (samples_done < 0) return fail(BSFA_ERR_SHAPE, "samples_done must be non-negative");

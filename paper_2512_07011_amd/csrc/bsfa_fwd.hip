@@ -89,6 +89,32 @@ __device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const int
     }
 }
 
+// The same copy for the last key block of a sequence that does not fill it: rows at and beyond
+// `rows` are fetched from row rows-1, which is the repeat-last-token padding of Section 4.3
+// (and keeps the copy inside the caller's buffers).  Same number of requests per lane as
+// tile_copy_async, so the vmcnt bookkeeping does not change.
+template <int D, int NT, bool ISV>
+__device__ __forceinline__ void tile_copy_async_clamped(const uint16_t *gtile, int stride_n, int rows,
+                                                        uint32_t lds_tile, int wave, int tid)
+{
+    constexpr int CPR = D / 8;
+    // the offsets are recomputed here, at the one place per sequence that needs them: the empty
+    // asm keeps the compiler from hoisting them out of the key loop into long-lived registers
+    asm volatile("" : "+v"(tid));
+#pragma unroll
+    for (int r = 0; r < 64 * CPR / NT; ++r) {
+        const int sigma = r * NT + tid;
+        const int row = sigma / CPR, cp = sigma % CPR;
+        const int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
+        const uint16_t *src = gtile + (min(row, rows - 1) * stride_n + 8 * c);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(dst), "v"(src)
+                     : "memory");
+    }
+}
+
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
@@ -206,7 +232,25 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     const bool stat_lane = (wrow == 0 && lane == 0);     // one lane per head writes statistics
 
     const int64_t row0 = (int64_t)i * BM;                 // first query row of the tile
-    const int n_blk = p.causal ? (int)((row0 + BM + BN - 1) / BN) : p.mkv;   // reachable blocks
+    // tokens of this batch element; a sequence that does not fill its last query tile or key
+    // block behaves as if padded by repeating its last token (Section 4.3): loads of rows
+    // beyond the end read row n_tok - 1 instead, padded rows are not stored, and key blocks made
+    // of padding only are not visited (the causal mask hides them from every real row).
+    int n_tok = p.seqlen;
+    if (p.seqlens) n_tok = min(max(__builtin_amdgcn_readfirstlane(p.seqlens[b]), 0), p.seqlen);
+    const int64_t stat_row = ((int64_t)b * p.hq + h) * p.mq + i;
+    if (row0 >= n_tok) {                                  // the tile lies beyond the sequence: empty statistics
+        const int htid = tid - hsel * NWH * 64;
+        if (p.block_max)
+            for (int jj = htid; jj < p.mkv; jj += NWH * 64) p.block_max[stat_row * p.mkv + jj] = NAN;
+        if (p.skip_mask)
+            for (int w = htid; w < p.mask_words; w += NWH * 64) p.skip_mask[stat_row * p.mask_words + w] = 0u;
+        return;
+    }
+    const int mkv_tok = (n_tok + BN - 1) / BN;
+    const int partial_blk = (n_tok % BN) ? n_tok / BN : -1;   // the block that padding completes, if any
+    const int partial_rows = n_tok % BN;
+    const int n_blk = p.causal ? min((int)((row0 + BM + BN - 1) / BN), mkv_tok) : mkv_tok;   // reachable blocks
     // causal: blocks [0, n_gate) are gateable, [n_gate, n_blk) touch the boundary.
     // non-causal: blocks [own_lo, own_hi) overlap the tile's own tokens and bypass the gate.
     const int n_gate = p.causal ? (int)((row0 + 1) / BN) : 0;
@@ -216,7 +260,8 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     const uint16_t *vbase = p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
     float tau_h[HP];                                      // thresholds of the group's heads for this tile
 #pragma unroll
-    for (int x = 0; x < HP; ++x) tau_h[x] = p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.mq + i : (h0 + x)];
+    for (int x = 0; x < HP; ++x)     // tiles past the calibrated length use its last tile's threshold (Section 4.3)
+        tau_h[x] = p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
 
     int koff[NST], voff[NST];
 #pragma unroll
@@ -225,6 +270,16 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         voff[r] = chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
     }
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
+    auto copy_k = [&](int t) {                            // K_t into its ring slot
+        const uint32_t dst = lds_k0 + (uint32_t)(t % KR) * TILE_BYTES;
+        if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave, tid);
+        else tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
+    };
+    auto copy_v = [&](int t) {                            // V_t into slot t & 1
+        const uint32_t dst = lds_v0 + (uint32_t)(t & 1) * TILE_BYTES;
+        if (t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave, tid);
+        else tile_copy_async<D, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);
+    };
 
     // Operand gather addresses (bytes inside a tile slot).
     // K (A operand of S^T): lane reads key row 32*kb + l32, chunk (2s + hh) ^ swz_k(row).  The row
@@ -251,7 +306,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     bf16x8 qreg[KS];
     const int q_row = (int)row0 + wrow * 32 + l32;
     {
-        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)q_row * p.qsn + (int64_t)h * p.qsh + 8 * hh;
+        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)min(q_row, n_tok - 1) * p.qsn + (int64_t)h * p.qsh + 8 * hh;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
     }
@@ -266,7 +321,6 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     unsigned n_skipped = 0;    // per-head statistics, uniform over the head's waves
     uint32_t mask_word = 0;
-    const int64_t stat_row = ((int64_t)b * p.hq + h) * p.mq + i;
 
     auto is_gated = [&](int j) { return p.causal ? (j < n_gate) : (j < own_lo || j >= own_hi); };
 
@@ -484,10 +538,11 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         wg_barrier();
         if (has_next) {
             decide(nxt, j + 1, fast_tag);
-            if (!CALIB && nxt.any_keep)
-                tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
-            if (j + R < n_blk)
-                tile_copy_async<D, NT>(kbase + (int64_t)(j + R) * kstep, koff, lds_k0 + (uint32_t)((j + R) % KR) * TILE_BYTES, wave);
+            if (!CALIB && nxt.any_keep) {
+                if constexpr (FAST) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
+                else copy_v(j + 1);                       // a gateable block is never the partial one
+            }
+            if (j + R < n_blk) copy_k(j + R);
         }
         if constexpr (!CALIB) {
             if (do_pv) pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES);
@@ -496,17 +551,17 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // ---- prologue: scores and decision of block 0, then K_1 .. K_{R-1} and V_0 -----------------
     ScoreTile ta, tb;
-    tile_copy_async<D, NT>(kbase, koff, lds_k0, wave);
+    copy_k(0);
     wait_vmcnt<0>();
     wg_barrier();
     qk_mfma(ta, lds_k0);
     reduce_scores(ta, 0, std::false_type{});
     wg_barrier();                                       // block maxima visible, K_0 consumed
     decide(ta, 0, std::false_type{});
-    if (!CALIB && ta.any_keep) tile_copy_async<D, NT>(vbase, voff, lds_v0, wave);
+    if (!CALIB && ta.any_keep) copy_v(0);
 #pragma unroll
     for (int t = 1; t < R; ++t)                            // K_{R-1} reuses the slot block 0 has just left
-        if (t < n_blk) tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, lds_k0 + (uint32_t)(t % KR) * TILE_BYTES, wave);
+        if (t < n_blk) copy_k(t);
     wait_vmcnt<0>();                                       // drained once; from here on the steady-state rule holds
     wg_barrier();
 
@@ -541,6 +596,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     if constexpr (!CALIB) {
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         const float inv = 1.0f / l_tot;
+        if (q_row >= n_tok) return;     // padding rows of the last tile are not stored
         if (p.lse && hh == 0)           // L = m + log(l); m_run is in log2 units
             p.lse[((int64_t)b * p.seqlen + q_row) * p.hq + h] = m_run * 0.6931471805599453f + __logf(l_tot);
         uint16_t *op = p.out + (int64_t)b * p.osb + (int64_t)q_row * p.osn + (int64_t)h * p.osh;

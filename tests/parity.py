@@ -39,11 +39,12 @@ class ParityReport:
 
 def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None, block_max_gpu=None,
             items=None, oracle_result=None, lse_gpu=None) -> ParityReport:
-    """q, k, v: the bf16 tensors the kernel saw (any device); tau numpy/torch [Hq] or [Hq, M_Q];
-    out_gpu [B,N,Hq,d]; skip_mask_gpu [B,Hq,M_Q,W]; block_max_gpu [B,Hq,M_Q,M_KV]."""
+    """q, k, v: the bf16 tensors the kernel saw (any device); tau numpy/torch [Hq] or [Hq, T];
+    out_gpu [B,N,Hq,d]; skip_mask_gpu [B,Hq,M_Q,W]; block_max_gpu [B,Hq,M_Q,M_KV].  N need not
+    fill its last tile: M_Q and M_KV are rounded up and the rows that do not exist are left out."""
     qf, kf, vf = (t.detach().float().cpu() for t in (q, k, v))
     B, N, Hq, d = qf.shape
-    mq, mkv = N // block_m, N // block_n
+    mq, mkv = -(-N // block_m), -(-N // block_n)
     tau = np.asarray(tau.detach().cpu() if hasattr(tau, "detach") else tau, dtype=np.float32)
     if items is None:
         items = [(b, h, i) for b in range(B) for h in range(Hq) for i in range(mq)]
@@ -51,7 +52,7 @@ def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None,
     r = oracle_result if oracle_result is not None else orc.forward_items(qf, kf, vf, tau, block_m, block_n, causal, items)
     ib, ih, ii = items[:, 0], items[:, 1], items[:, 2]
 
-    tau_item = tau[ih, ii] if tau.ndim == 2 else tau[ih]
+    tau_item = tau[ih, np.minimum(ii, tau.shape[1] - 1)] if tau.ndim == 2 else tau[ih]
     gate = (r.cls == orc.CLS_SKIPPED) | (r.cls == orc.CLS_KEPT)
     band = gate & (np.abs(r.bmax - tau_item[:, None]) <= BAND)
     mismatch = 0
@@ -72,18 +73,29 @@ def compare(q, k, v, tau, block_m, block_n, causal, out_gpu, skip_mask_gpu=None,
         bmax_err = float(np.nanmax(np.abs(bg - r.bmax))) if gate.any() else 0.0
         assert bmax_err <= 1e-4 * max(1.0, float(np.nanmax(np.abs(r.bmax))) if gate.any() else 1.0), "block maxima differ by %g" % bmax_err
     if lse_gpu is not None:
-        lg = lse_gpu.detach().cpu().numpy().reshape(B, mq, block_m, Hq)[ib, ii, :, ih]   # [n, BM]
-        lse_err = float(np.abs(lg - ref.lse).max())
+        lg = _tile_rows(lse_gpu.detach().cpu().numpy()[..., None], mq, block_m)[ib, ii, :, ih, 0]   # [n, BM]
+        real = ~np.isnan(ref.lse)
+        assert np.isfinite(lg[real]).all(), "non-finite log-sum-exp"
+        lse_err = float(np.abs(lg - ref.lse)[real].max())
         assert lse_err <= 5e-3, "log-sum-exp differs by %g" % lse_err
-    og = out_gpu.detach().float().cpu().numpy()
-    og = og.reshape(B, mq, block_m, Hq, d)[ib, ii, :, ih]                                # [n, BM, d]
-    assert np.isfinite(og).all(), "non-finite output"
-    err = np.abs(og - ref.out)
+    og = _tile_rows(out_gpu.detach().float().cpu().numpy(), mq, block_m)[ib, ii, :, ih]  # [n, BM, d]
+    real = ~np.isnan(ref.out)                                                            # rows that exist
+    assert np.isfinite(og[real]).all(), "non-finite output"
+    err = np.abs(og - ref.out)[real]
     rep = ParityReport(len(items), float(err.max()), float(err.mean()), mismatch, int(band.sum()), bmax_err,
                        int((ref.cls == orc.CLS_SKIPPED).sum()), int(gate.sum()))
     assert rep.max_abs <= MAX_ABS, "max-abs error %g > %g" % (rep.max_abs, MAX_ABS)
     assert rep.mean_abs <= MEAN_ABS, "mean-abs error %g > %g" % (rep.mean_abs, MEAN_ABS)
     return rep
+
+
+def _tile_rows(x: np.ndarray, mq: int, block_m: int) -> np.ndarray:
+    """[B, N, H, c] -> [B, mq, block_m, H, c], the rows past N filled with NaN."""
+    B, N = x.shape[:2]
+    if mq * block_m != N:
+        pad = np.full((B, mq * block_m - N) + x.shape[2:], np.nan, x.dtype)
+        x = np.concatenate([x, pad], axis=1)
+    return x.reshape(B, mq, block_m, *x.shape[2:])
 
 
 def sample_items(shape, n_random=5, seed=0):

@@ -49,10 +49,10 @@ FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
 
 
 @pytest.mark.parametrize("kw, code", [
-    (dict(batch=0), -2), (dict(seqlen=500), -2), (dict(n_q_heads=3), -2), (dict(dtype=7), -3),
+    (dict(batch=0), -2), (dict(seqlen=0), -2), (dict(n_q_heads=3), -2), (dict(dtype=7), -3),
     (dict(head_dim=96), -4), (dict(block_m=96), -4), (dict(block_n=32), -4), (dict(block_m=256), -4),
     (dict(q_stride_n=516), -2), (dict(k_stride_h=64), -2), (dict(thresholds_per_tile=2), -2),
-    (dict(o_stride_b=-8), -2),
+    (dict(o_stride_b=-8), -2), (dict(threshold_tiles=-1), -2), (dict(seqlens=0x1002), -2),
 ])
 def test_forward_rejects_bad_problems(lib, kw, code):
     p = good_problem(**kw)
@@ -60,6 +60,17 @@ def test_forward_rejects_bad_problems(lib, kw, code):
     assert rc == code, (kw, rc, lib.bsfa_last_error())
     assert lib.bsfa_last_error() != b""
     assert lib.bsfa_calibrate_workspace_bytes(ctypes.byref(p)) == 0
+
+
+def test_ragged_lengths_need_the_causal_mask(lib):
+    """Without the causal mask padded keys would be visible: a sequence that does not fill its
+    last block, or per-element lengths, are rejected there (and accepted with the mask: checked on
+    the GPU, where the pointers are real)."""
+    for kw in (dict(seqlen=500), dict(seqlen=544), dict(seqlens=0x1000)):
+        p = good_problem(**kw)
+        assert lib.bsfa_forward(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, 0, FAKE, None, None) == -2, kw
+    # the workspace query assumes the causal mask: ceil(500/128) x ceil(500/64) maxima per head
+    assert lib.bsfa_calibrate_workspace_bytes(ctypes.byref(good_problem(seqlen=500))) >= 4 * 4 * 8 * 4
 
 
 def test_null_and_alignment(lib):
@@ -97,7 +108,8 @@ def test_calibrate_topk_argument_checks(lib):
     assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, ks, 2, -1, out, FAKE, need, None) == -2
     neg = (ctypes.c_int32 * 1)(-3)
     assert lib.bsfa_calibrate_topk(ctypes.byref(p), FAKE, FAKE, 1, neg, 1, 0, out, FAKE, need, None) == -2
-    assert lib.bsfa_calibrate_topk(ctypes.byref(good_problem(seqlen=500)), FAKE, FAKE, 1, ks, 2, 0, out, FAKE, need, None) == -2
+    assert lib.bsfa_calibrate_topk(ctypes.byref(good_problem(seqlen=500)), FAKE, FAKE, 0, ks, 2, 0, out, FAKE, need, None) == -2
+    assert lib.bsfa_calibrate_topk(ctypes.byref(good_problem(seqlens=0x1000)), FAKE, FAKE, 1, ks, 2, 0, out, FAKE, need, None) == -4
 
 
 def test_query_build_and_status_strings(lib):
