@@ -57,34 +57,34 @@ template <int D> __device__ __forceinline__ int swz_v(int row)
     return (D == 128) ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
 }
 
-// Element offset (relative to the tile's first row) of the chunk thread `tid` copies in
-// repetition r.
+// Byte offset (relative to the tile's first row) of the chunk thread `tid` copies in
+// repetition r; rows at and beyond `rows` are fetched from row rows - 1.
 template <int D, int NT, bool ISV>
-__device__ __forceinline__ int chunk_src_offset(int r, int tid, int stride_n)
+__device__ __forceinline__ uint32_t chunk_src_offset(int r, int tid, int stride_n, int rows = 64)
 {
     constexpr int CPR = D / 8;
     const int sigma = r * NT + tid;
     const int row = sigma / CPR, cp = sigma % CPR;
     const int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
-    return row * stride_n + 8 * c;
+    return (uint32_t)(min(row, rows - 1) * stride_n + 8 * c) * 2u;
 }
 
 // Asynchronous HBM -> LDS copy of one 64 x D tile; lds_tile is the byte address of the tile's
-// slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  Completion is
-// tracked by vmcnt, which this kernel manages itself (wait_vmcnt): the instruction is emitted
-// through inline asm so that the compiler does not serialise every later LDS read behind all
-// copies in flight.
+// slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  The tile's first
+// row is addressed through a scalar base (it is the same for the whole workgroup), each lane adds
+// its 32-bit byte offset.  Completion is tracked by vmcnt, which this kernel manages itself
+// (wait_vmcnt): the instruction is emitted through inline asm so that the compiler does not
+// serialise every later LDS read behind all copies in flight.
 template <int D, int NT>
-__device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const int (&off)[64 * (D / 8) / NT],
+__device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const uint32_t (&off)[64 * (D / 8) / NT],
                                                 uint32_t lds_tile, int wave)
 {
 #pragma unroll
     for (int r = 0; r < 64 * (D / 8) / NT; ++r) {
-        const uint16_t *src = gtile + off[r];
         const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
-                     : "s"(dst), "v"(src)
+                     : "s"(dst), "v"(off[r]), "s"(gtile)
                      : "memory");
     }
 }
@@ -92,27 +92,18 @@ __device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const int
 // The same copy for the last key block of a sequence that does not fill it: rows at and beyond
 // `rows` are fetched from row rows-1, which is the repeat-last-token padding of Section 4.3
 // (and keeps the copy inside the caller's buffers).  Same number of requests per lane as
-// tile_copy_async, so the vmcnt bookkeeping does not change.
+// tile_copy_async, so the vmcnt bookkeeping does not change.  The offsets are computed here, at
+// the one place per sequence that needs them, from the lane id (no long-lived registers).
 template <int D, int NT, bool ISV>
 __device__ __forceinline__ void tile_copy_async_clamped(const uint16_t *gtile, int stride_n, int rows,
-                                                        uint32_t lds_tile, int wave, int tid)
+                                                        uint32_t lds_tile, int wave)
 {
-    constexpr int CPR = D / 8;
-    // the offsets are recomputed here, at the one place per sequence that needs them: the empty
-    // asm keeps the compiler from hoisting them out of the key loop into long-lived registers
-    asm volatile("" : "+v"(tid));
+    int tid = wave * 64 + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(tid));       // keeps the offsets from being hoisted out of the key loop
+    uint32_t off[64 * (D / 8) / NT];
 #pragma unroll
-    for (int r = 0; r < 64 * CPR / NT; ++r) {
-        const int sigma = r * NT + tid;
-        const int row = sigma / CPR, cp = sigma % CPR;
-        const int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
-        const uint16_t *src = gtile + (min(row, rows - 1) * stride_n + 8 * c);
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                     :
-                     : "s"(dst), "v"(src)
-                     : "memory");
-    }
+    for (int r = 0; r < 64 * (D / 8) / NT; ++r) off[r] = chunk_src_offset<D, NT, ISV>(r, tid, stride_n, rows);
+    tile_copy_async<D, NT>(gtile, off, lds_tile, wave);
 }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)
@@ -263,7 +254,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     for (int x = 0; x < HP; ++x)     // tiles past the calibrated length use its last tile's threshold (Section 4.3)
         tau_h[x] = p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
 
-    int koff[NST], voff[NST];
+    uint32_t koff[NST], voff[NST];
 #pragma unroll
     for (int r = 0; r < NST; ++r) {
         koff[r] = chunk_src_offset<D, NT, false>(r, tid, (int)p.ksn);
@@ -272,12 +263,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
     auto copy_k = [&](int t) {                            // K_t into its ring slot
         const uint32_t dst = lds_k0 + (uint32_t)(t % KR) * TILE_BYTES;
-        if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave, tid);
+        if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
         else tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
     };
     auto copy_v = [&](int t) {                            // V_t into slot t & 1
         const uint32_t dst = lds_v0 + (uint32_t)(t & 1) * TILE_BYTES;
-        if (t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave, tid);
+        if (t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave);
         else tile_copy_async<D, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);
     };
 
@@ -379,8 +370,10 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         }
     };
 
-    // gate decisions for block j (after the barrier that publishes lds_red[j & 1]) + statistics
-    auto decide = [&](ScoreTile &t, int j, auto fast_tag) {
+    // gate decisions for block j + statistics.  `red` holds the waves' block maxima, read from
+    // lds_red[j & 1] after the barrier that publishes them (the read is issued early by the caller
+    // so that its latency is covered)
+    auto decide = [&](ScoreTile &t, int j, const float (&red)[NW], auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         bool keep = true, any_keep = true;
         float bmax = NAN;
@@ -388,9 +381,9 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             any_keep = false;
 #pragma unroll
             for (int x = 0; x < HP; ++x) {
-                float r = lds_red[j & 1][x * NWH];
+                float r = red[x * NWH];
 #pragma unroll
-                for (int w = 1; w < NWH; ++w) r = fmaxf(r, lds_red[j & 1][x * NWH + w]);
+                for (int w = 1; w < NWH; ++w) r = fmaxf(r, red[x * NWH + w]);
                 const float sm = r * p.scale;                        // natural score units (Eq. 5-6)
                 const bool kx = (sm >= tau_h[x]);                    // skip iff s_max < T
                 any_keep = any_keep || kx;
@@ -483,7 +476,10 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // O^T += V^T P^T for the V tile at LDS byte address `vt`; operand n = (k-step u = n / DB,
     // head-dim block x = n % DB), read PD MFMAs ahead
-    auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt) {
+    // `mid` runs after the first PV_MID MFMAs have been issued (work that only has to happen
+    // soon after the barrier goes there, beside the matrix pipe instead of in front of it)
+    constexpr int PV_MID = 4;
+    auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt, auto mid) {
         const uint32_t vaddr = vt + va_base;
         auto v_operand = [&](int n) {
             const int u = n / DB, x = n % DB;
@@ -502,6 +498,10 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             if (n + PD < 4 * DB) a[n + PD] = v_operand(n + PD);
             oacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], pb[n / DB], oacc[n % DB], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+            if (n == PV_MID - 1) {
+                mid();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
 
@@ -536,16 +536,27 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             wait_vmcnt<0>();
         }
         wg_barrier();
+        float red[NW];
         if (has_next) {
-            decide(nxt, j + 1, fast_tag);
-            if (!CALIB && nxt.any_keep) {
-                if constexpr (FAST) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
-                else copy_v(j + 1);                       // a gateable block is never the partial one
-            }
-            if (j + R < n_blk) copy_k(j + R);
+#pragma unroll
+            for (int w = 0; w < NW; ++w) red[w] = lds_red[(j + 1) & 1][w];
         }
-        if constexpr (!CALIB) {
-            if (do_pv) pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES);
+        __builtin_amdgcn_sched_barrier(0);
+        // decision for block j+1, then the requests for V_{j+1} and K_{j+R}
+        auto look_ahead = [&]() {
+            if (has_next) {
+                decide(nxt, j + 1, red, fast_tag);
+                if (!CALIB && nxt.any_keep) {
+                    if constexpr (FAST) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
+                    else copy_v(j + 1);                   // a gateable block is never the partial one
+                }
+                if (j + R < n_blk) copy_k(j + R);
+            }
+        };
+        if (do_pv) {
+            if constexpr (!CALIB) pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES, look_ahead);
+        } else {
+            look_ahead();
         }
     };
 
@@ -557,7 +568,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     qk_mfma(ta, lds_k0);
     reduce_scores(ta, 0, std::false_type{});
     wg_barrier();                                       // block maxima visible, K_0 consumed
-    decide(ta, 0, std::false_type{});
+    {
+        float red[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) red[w] = lds_red[0][w];
+        decide(ta, 0, red, std::false_type{});
+    }
     if (!CALIB && ta.any_keep) copy_v(0);
 #pragma unroll
     for (int t = 1; t < R; ++t)                            // K_{R-1} reuses the slot block 0 has just left
@@ -649,8 +665,8 @@ bool shape_supported(int head_dim, int block_m, int block_n)
 hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool calib, hipStream_t stream)
 {
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
-    // the copies address a tile with 32-bit element offsets
-    if (p.ksn * 64 > 0x7fffffffLL || p.vsn * 64 > 0x7fffffffLL) return hipErrorInvalidValue;
+    // the copies address a tile with 32-bit byte offsets
+    if (p.ksn * 128 > 0x7fff0000LL || p.vsn * 128 > 0x7fff0000LL) return hipErrorInvalidValue;
     const bool pair_heads = (p.group % 2 == 0);
 #define BSFA_CASE(DD, NN, HH, KK) \
     if (head_dim == DD && block_m == 32 * NN) return launch_t<DD, NN, HH, KK>(p, calib, stream);
