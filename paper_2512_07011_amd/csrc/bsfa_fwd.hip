@@ -187,6 +187,8 @@ struct ScoreTile {
     float mx;             // row max of the lane's query, equal in lanes l and l^32
     bool keep;            // gate decision of this wave's head (uniform over the head's waves)
     bool any_keep;        // some head of the workgroup keeps the block (workgroup-uniform): V is fetched
+    float m_use;          // kept blocks: row max the exponentials are taken against (log2 units)
+    float alpha;          // kept blocks: factor that rescales the running accumulator and normaliser
 };
 
 template <int D, int NWH, int HP, int KR, bool CALIB>
@@ -261,8 +263,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         voff[r] = chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
     }
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
-    auto copy_k = [&](int t) {                            // K_t into its ring slot
-        const uint32_t dst = lds_k0 + (uint32_t)(t % KR) * TILE_BYTES;
+    auto copy_k = [&](int t, uint32_t dst) {              // K_t into the ring slot at LDS byte address dst
         if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
         else tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
     };
@@ -406,12 +407,11 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // online-softmax update of the running statistics with block `t`: new row max and the
     // accumulator's rescale factor first, then the exponentials, P (bf16) into pb
-    auto softmax_begin = [&](ScoreTile &t, float &m_use) -> float {
+    auto softmax_begin = [&](ScoreTile &t) {
         const float m_new = fmaxf(m_run, t.mx * p.scale_log2);
-        m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        t.m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        t.alpha = __builtin_amdgcn_exp2f(m_run - t.m_use);
         m_run = m_new;
-        return alpha;
     };
     auto softmax_exp = [&](ScoreTile &t, float m_use, float alpha, bf16x8 (&pb)[4]) {
         float psum = 0.f;
@@ -505,6 +505,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         }
     };
 
+    uint32_t kring = (uint32_t)(1 % KR) * TILE_BYTES;     // ring offset of the K slot the next stage reads
     // One pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`).
     // FAST: block j+1 exists and is gateable, so the look-ahead has no mask and no conditionals.
     auto stage = [&](ScoreTile &cur, ScoreTile &nxt, int j, auto fast_tag) {
@@ -512,10 +513,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const bool has_next = FAST || (j + 1 < n_blk);
         bf16x8 pb[4];
         const bool do_pv = !CALIB && cur.keep;
-        const uint32_t kt_next = lds_k0 + (uint32_t)((j + 1) % KR) * TILE_BYTES;
+        // slot of K_{j+1}; K_{j+R} is requested into the same slot once block j+1 has left it
+        // (R = KR + 1), so one ring position per stage is all the bookkeeping there is
+        const uint32_t kt_next = lds_k0 + kring;
+        kring = (kring + TILE_BYTES == KR * TILE_BYTES) ? 0u : kring + TILE_BYTES;
         if (do_pv) {
-            float m_use;
-            const float alpha = softmax_begin(cur, m_use);
+            const float m_use = cur.m_use, alpha = cur.alpha;
             rescale(alpha);                       // the previous block's PV has been issued already
             if constexpr (FAST) {
                 fused_exp_qk(cur, nxt, kt_next, m_use, alpha, pb);
@@ -546,11 +549,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         auto look_ahead = [&]() {
             if (has_next) {
                 decide(nxt, j + 1, red, fast_tag);
+                if (!CALIB && nxt.keep) softmax_begin(nxt);   // running max and rescale factor, off the critical path
                 if (!CALIB && nxt.any_keep) {
                     if constexpr (FAST) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
                     else copy_v(j + 1);                   // a gateable block is never the partial one
                 }
-                if (j + R < n_blk) copy_k(j + R);
+                if (j + R < n_blk) copy_k(j + R, kt_next);
             }
         };
         if (do_pv) {
@@ -562,7 +566,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // ---- prologue: scores and decision of block 0, then K_1 .. K_{R-1} and V_0 -----------------
     ScoreTile ta, tb;
-    copy_k(0);
+    copy_k(0, lds_k0);
     wait_vmcnt<0>();
     wg_barrier();
     qk_mfma(ta, lds_k0);
@@ -573,11 +577,12 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
         for (int w = 0; w < NW; ++w) red[w] = lds_red[0][w];
         decide(ta, 0, red, std::false_type{});
+        if (!CALIB && ta.keep) softmax_begin(ta);
     }
     if (!CALIB && ta.any_keep) copy_v(0);
 #pragma unroll
     for (int t = 1; t < R; ++t)                            // K_{R-1} reuses the slot block 0 has just left
-        if (t < n_blk) copy_k(t);
+        if (t < n_blk) copy_k(t, lds_k0 + (uint32_t)(t % KR) * TILE_BYTES);
     wait_vmcnt<0>();                                       // drained once; from here on the steady-state rule holds
     wg_barrier();
 
