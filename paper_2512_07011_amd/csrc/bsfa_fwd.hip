@@ -444,24 +444,37 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
             for (int e = 0; e < 16; ++e) nxt.s[kb][e] = 0.f;
         constexpr int EPM = 32 / (2 * KS);         // exponentials per MFMA (2 at D = 128, 4 at D = 64)
-#pragma unroll
-        for (int n = 0; n < 2 * KS; ++n) {
-            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
-            nxt.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], nxt.s[n & 1], 0, 0, 0);
+        // The exponentials of one MFMA slot are rounded, packed and summed one slot later, so that
+        // no instruction waits for a transcendental issued just before it.
+        float ex[EPM];
+        auto pack = [&](int n) {                   // the pairs computed in slot n
 #pragma unroll
             for (int t = 0; t < EPM; t += 2) {
-                const int idx = n * EPM + t, kb = idx >> 4, e = idx & 15;
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e], p.scale_log2, -m_use));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(cur.s[kb][e + 1], p.scale_log2, -m_use));
-                const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+                const int idx = n * EPM + t;
+                const bf16x2 pp = {(__bf16)ex[t], (__bf16)ex[t + 1]};
                 // row sum of the rounded values (the ones the second MFMA multiplies): p0 + p1 + acc
                 if (t & 2) psum1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum1, false);
                 else psum0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum0, false);
                 pb[idx >> 3][idx & 7] = pp[0];
                 pb[idx >> 3][(idx & 7) + 1] = pp[1];
             }
+        };
+#pragma unroll
+        for (int n = 0; n < 2 * KS; ++n) {
+            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
+            nxt.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], nxt.s[n & 1], 0, 0, 0);
+            float nx[EPM];
+#pragma unroll
+            for (int t = 0; t < EPM; ++t) {
+                const int idx = n * EPM + t;
+                nx[t] = __builtin_amdgcn_exp2f(fmaf(cur.s[idx >> 4][idx & 15], p.scale_log2, -m_use));
+            }
+            if (n > 0) pack(n - 1);
+#pragma unroll
+            for (int t = 0; t < EPM; ++t) ex[t] = nx[t];
             __builtin_amdgcn_sched_barrier(0);
         }
+        pack(2 * KS - 1);
         l_run = l_run * alpha + (psum0 + psum1);
     };
 
