@@ -51,7 +51,10 @@ typedef enum {
     BSFA_ERR_HIP = -6          /* a HIP runtime call failed (message in bsfa_last_error)  */
 } bsfa_status;
 
-typedef enum { BSFA_BF16 = 0 } bsfa_dtype; /* inputs/outputs bf16, fp32 accumulation */
+/* Element type of q, k, v and out.  Scores, the gate comparison, the running statistics and both
+ * accumulators are fp32 in either case; the probabilities are rounded to the element type for the
+ * second product.  fp16 is the precision of the paper's own kernel (Section 5.1). */
+typedef enum { BSFA_BF16 = 0, BSFA_FP16 = 1 } bsfa_dtype;
 
 /* Problem descriptor (paper notation, Section 2.2: N tokens, head dim d, query tiles of B_M
  * rows, key/value blocks of B_N rows).  Zero-initialise it: a zero in an optional member selects

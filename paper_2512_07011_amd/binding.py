@@ -21,6 +21,14 @@ EXPORTS = ["bsfa_forward", "bsfa_calibrate", "bsfa_calibrate_topk", "bsfa_calibr
            "bsfa_status_string", "bsfa_last_error"]
 
 
+DTYPES = {torch.bfloat16: 0, torch.float16: 1}       # bsfa_dtype
+
+
+def _same_16bit(name, *ts):
+    if ts[0].dtype not in DTYPES or any(t.dtype != ts[0].dtype for t in ts):
+        raise TypeError("%s: tensors must all be bfloat16 or all float16" % name)
+
+
 class BsfaError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__("%s: %s" % (STATUS_NAMES.get(status, str(status)), message))
@@ -98,7 +106,7 @@ def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], ou
         setattr(p, name + "_stride_b", t.stride(0))
         setattr(p, name + "_stride_n", t.stride(1))
         setattr(p, name + "_stride_h", t.stride(2))
-    p.dtype = 0
+    p.dtype = DTYPES[q.dtype]
     p.thresholds_per_tile = int(thresholds_per_tile)
     p.threshold_tiles = int(threshold_tiles)
     if seqlens is not None:
@@ -148,13 +156,12 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
                  stream: Optional[torch.cuda.Stream] = None,
                  seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """out = block-sparse attention of bf16 q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
+    """out = block-sparse attention of bf16 (or fp16) q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
     GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
     GPU tensor [B], causal only) gives each batch element its own length.  Enqueues on
     ``stream`` (default: torch's current stream)."""
     _dev_check(q, k, v, thresholds, out)
-    if not (q.dtype == k.dtype == v.dtype == torch.bfloat16):
-        raise TypeError("bsfa_forward: q, k, v must be bfloat16")
+    _same_16bit("bsfa_forward", q, k, v, *([out] if out is not None else []))
     if thresholds.dtype != torch.float32 or not thresholds.is_contiguous():
         raise TypeError("bsfa_forward: thresholds must be contiguous float32")
     per_tile = thresholds.dim() == 2
@@ -185,8 +192,7 @@ def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequ
                    seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Per-head thresholds for each target skip fraction: CPU float32 tensor [n_levels, Hq]."""
     _dev_check(q, k, workspace)
-    if not (q.dtype == k.dtype == torch.bfloat16):
-        raise TypeError("bsfa_calibrate: q, k must be bfloat16")
+    _same_16bit("bsfa_calibrate", q, k)
     p = make_problem(q, k, None, None, block_m, block_n, seqlens=seqlens)
     need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
     if need == 0:
@@ -215,8 +221,7 @@ def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m
     kk = (ctypes.c_int32 * n)(*[int(x) for x in ks])
     for q, k in samples:
         _dev_check(q, k)
-        if not (q.dtype == k.dtype == torch.bfloat16):
-            raise TypeError("bsfa_calibrate_topk: q, k must be bfloat16")
+        _same_16bit("bsfa_calibrate_topk", q, k)
         p = make_problem(q, k, None, None, block_m, block_n)
         need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
         if ws is None or ws.numel() < need:

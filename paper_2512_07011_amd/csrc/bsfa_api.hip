@@ -28,7 +28,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bsfa_status check_problem(const bsfa_problem *p, int causal)
 {
     if (!p) return fail(BSFA_ERR_NULL, "problem descriptor is NULL");
-    if (p->dtype != BSFA_BF16) return fail(BSFA_ERR_DTYPE, "dtype %d not supported (bf16 only)", p->dtype);
+    if (p->dtype != BSFA_BF16 && p->dtype != BSFA_FP16) return fail(BSFA_ERR_DTYPE, "dtype %d not supported (bf16 and fp16 only)", p->dtype);
     if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->seqlen < 1 || p->head_dim < 1)
         return fail(BSFA_ERR_SHAPE, "batch, head counts, seqlen and head_dim must be positive");
     if (p->n_q_heads % p->n_kv_heads)
@@ -71,6 +71,7 @@ void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
     fp.tau_tiles = p->threshold_tiles > 0 ? p->threshold_tiles : fp.mq;
     fp.mask_words = (fp.mkv + 31) / 32;
     fp.causal = causal ? 1 : 0;
+    fp.f16 = (p->dtype == BSFA_FP16) ? 1 : 0;
     fp.tau_per_tile = p->thresholds_per_tile;
     fp.scale = 1.0f / sqrtf((float)p->head_dim);
     fp.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->head_dim));

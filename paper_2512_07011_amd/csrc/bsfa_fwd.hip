@@ -31,10 +31,40 @@
 
 namespace bsfa {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// The 16-bit element type of Q, K, V, P and O: bf16 or fp16 (the paper's kernel is fp16
+// throughout, Section 5.1).  Same storage size, same MFMA shape, same LDS layout; only the
+// matrix instruction, the pack and the pair sum differ.
+template <bool F16> struct Elem;
+template <> struct Elem<false> {
+    typedef __bf16 T;
+    typedef __bf16 x8 __attribute__((ext_vector_type(8)));
+    typedef __bf16 x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 x2 __attribute__((ext_vector_type(2)));
+};
+template <> struct Elem<true> {
+    typedef _Float16 T;
+    typedef _Float16 x8 __attribute__((ext_vector_type(8)));
+    typedef _Float16 x4 __attribute__((ext_vector_type(4)));
+    typedef _Float16 x2 __attribute__((ext_vector_type(2)));
+};
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+// 32x32x16 MFMA, fp32 accumulate, and p0 + p1 + acc on a packed pair: one overload per element type
+__device__ __forceinline__ f32x16 mfma16(bf16x8_t a, bf16x8_t b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ f32x16 mfma16(f16x8_t a, f16x8_t b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ float pair_sum(bf16x2_t pp, float acc)
+{
+    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(pp, ones, acc, false);
+}
+__device__ __forceinline__ float pair_sum(f16x2_t pp, float acc)
+{
+    const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(pp, ones, acc, false);
+}
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -191,9 +221,13 @@ struct ScoreTile {
     float alpha;          // kept blocks: factor that rescales the running accumulator and normaliser
 };
 
-template <int D, int NWH, int HP, int KR, bool CALIB>
+template <int D, int NWH, int HP, int KR, bool CALIB, bool F16>
 __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdParams p)
 {
+    typedef typename Elem<F16>::T el;                    // element type of Q, K, V, P, O
+    typedef typename Elem<F16>::x8 bf16x8;               // (the vector names keep the default type's name)
+    typedef typename Elem<F16>::x4 bf16x4;
+    typedef typename Elem<F16>::x2 bf16x2;
     constexpr int NW = NWH * HP;
     constexpr int NT = NW * 64;
     constexpr int BM = NWH * 32;
@@ -338,7 +372,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
         for (int n = 0; n < 2 * KS; ++n) {
             if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
-            t.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], t.s[n & 1], 0, 0, 0);
+            t.s[n & 1] = mfma16(a[n], qreg[n >> 1], t.s[n & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -415,14 +449,13 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     };
     auto softmax_exp = [&](ScoreTile &t, float m_use, float alpha, bf16x8 (&pb)[4]) {
         float psum = 0.f;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int idx = 0; idx < 32; idx += 2) {
             const int kb = idx >> 4, e = idx & 15;
             const float p0 = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e], p.scale_log2, -m_use));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(t.s[kb][e + 1], p.scale_log2, -m_use));
-            const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
-            psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);   // sum of the rounded values
+            const bf16x2 pp = {(el)p0, (el)p1};
+            psum = pair_sum(pp, psum);                                       // sum of the rounded values
             pb[idx >> 3][idx & 7] = pp[0];
             pb[idx >> 3][(idx & 7) + 1] = pp[1];
         }
@@ -438,7 +471,6 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
         for (int n = 0; n < PD; ++n) a[n] = k_operand(kaddr, n);
         float psum0 = 0.f, psum1 = 0.f;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -451,10 +483,10 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
             for (int t = 0; t < EPM; t += 2) {
                 const int idx = n * EPM + t;
-                const bf16x2 pp = {(__bf16)ex[t], (__bf16)ex[t + 1]};
+                const bf16x2 pp = {(el)ex[t], (el)ex[t + 1]};
                 // row sum of the rounded values (the ones the second MFMA multiplies): p0 + p1 + acc
-                if (t & 2) psum1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum1, false);
-                else psum0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum0, false);
+                if (t & 2) psum1 = pair_sum(pp, psum1);
+                else psum0 = pair_sum(pp, psum0);
                 pb[idx >> 3][idx & 7] = pp[0];
                 pb[idx >> 3][(idx & 7) + 1] = pp[1];
             }
@@ -462,7 +494,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
         for (int n = 0; n < 2 * KS; ++n) {
             if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
-            nxt.s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], qreg[n >> 1], nxt.s[n & 1], 0, 0, 0);
+            nxt.s[n & 1] = mfma16(a[n], qreg[n >> 1], nxt.s[n & 1]);
             float nx[EPM];
 #pragma unroll
             for (int t = 0; t < EPM; ++t) {
@@ -509,7 +541,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
         for (int n = 0; n < 4 * DB; ++n) {
             if (n + PD < 4 * DB) a[n + PD] = v_operand(n + PD);
-            oacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n], pb[n / DB], oacc[n % DB], 0, 0, 0);
+            oacc[n % DB] = mfma16(a[n], pb[n / DB], oacc[n % DB]);
             __builtin_amdgcn_sched_barrier(0);
             if (n == PV_MID - 1) {
                 mid();
@@ -643,7 +675,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                 const int d0 = X_COLS * x + (m0 < 16 ? m0 : G16_COLS + m0 - 16);
                 bf16x4 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[x][4 * e4 + e] * inv);
+                for (int e = 0; e < 4; ++e) o[e] = (el)(oacc[x][4 * e4 + e] * inv);
                 *reinterpret_cast<bf16x4 *>(op + d0) = o;
             }
     }
@@ -653,6 +685,16 @@ __global__ void zero_counts_kernel(unsigned long long *c, int n)
 {
     int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n) c[t] = 0ull;
+}
+
+template <int D, int NWH, int HP, int KR, bool F16>
+static hipError_t launch_k(const FwdParams &p, bool calib, hipStream_t stream, long grid)
+{
+    if (calib)
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true, F16>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+    else
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false, F16>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+    return hipGetLastError();
 }
 
 template <int D, int NWH, int HP, int KR>
@@ -666,11 +708,7 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
-    if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
-    else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
-    return hipGetLastError();
+    return p.f16 ? launch_k<D, NWH, HP, KR, true>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false>(p, calib, stream, grid);
 }
 
 bool shape_supported(int head_dim, int block_m, int block_n)

@@ -9,13 +9,14 @@ namespace bsfa {
 constexpr int kBlockN = 64;
 
 struct FwdParams {
-    const uint16_t *q, *k, *v;       // bf16 bit patterns
+    const uint16_t *q, *k, *v;       // bf16 or fp16 bit patterns (f16 says which)
     uint16_t *out;
     const float *tau;                // [hq] or [hq][tau_tiles]
     const int32_t *seqlens;          // [batch] tokens per batch element, or null (all have seqlen)
     int64_t qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;
     int batch, hq, hkv, group, seqlen, mq, mkv;
     int causal, tau_per_tile, tau_tiles;
+    int f16;                         // element type of q, k, v, out: 0 bf16, 1 fp16
     float scale;                     // 1/sqrt(d): natural score units, used by the gate
     float scale_log2;                // log2(e)/sqrt(d): softmax evaluated with exp2
     unsigned long long *counts;      // [batch][hq][3] or null

@@ -197,3 +197,36 @@ def test_calibrate_topk_matches_section_4_2_rule(oracle):
         c = st.counts.cpu().numpy()
         dens = 1 - c[..., 0].sum() / c[..., 2].sum()
         assert abs(dens - oracle.predicted_density(2048, 128, 64, kk)) <= (rep.mask_mismatch + 0.5) / c[..., 2].sum()
+
+
+F16_SHAPES = [
+    (1, 512, 4, 2, 128, 128, 64),
+    (2, 384, 4, 1, 64, 64, 64),
+    (1, 320, 3, 1, 128, 32, 64),
+    (1, 1152, 16, 8, 128, 128, 64),
+]
+
+
+@pytest.mark.parametrize("case", F16_SHAPES)
+def test_fp16_inputs(oracle, case):
+    """fp16 Q/K/V/O (the precision of the paper's kernel, Section 5.1): same path, same tolerances;
+    both sides get the fp16-rounded values.  Dense, gated, and a sequence with a partial last block."""
+    shp = synth.Shape(*case)
+    q, k, v = synth.tiny(sum(case) + 1, shp, n_boost=max(1, shp.m_kv // 3))
+    qd, kd, vd = (t.to(torch.float16).to(DEV) for t in (q, k, v))
+    bm, bn = shp.block_m, shp.block_n
+    neg = torch.full((shp.n_q_heads,), float("-inf"), device=DEV)
+    out, st = run_gpu(qd, kd, vd, neg, bm, bn)
+    assert out.dtype == torch.float16
+    rep = parity.compare(qd, kd, vd, neg, bm, bn, True, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
+    assert rep.skipped == 0
+    tau = binding.bsfa_calibrate(qd, kd, [0.5], block_m=bm, block_n=bn)[0]
+    out, st = run_gpu(qd, kd, vd, tau.to(DEV), bm, bn)
+    rep = parity.compare(qd, kd, vd, tau, bm, bn, True, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
+    assert rep.skipped > 0
+    n = shp.seqlen - 37
+    qr, kr, vr = (t[:, :n].contiguous() for t in (qd, kd, vd))
+    out, st = run_gpu(qr, kr, vr, tau.to(DEV), bm, bn, dump=False)
+    parity.compare(qr, kr, vr, tau, bm, bn, True, out, st.skip_mask)
+    with pytest.raises(TypeError):
+        binding.bsfa_forward(qd, kd.to(torch.bfloat16), vd, neg, block_m=bm, block_n=bn)
