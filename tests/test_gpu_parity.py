@@ -230,3 +230,37 @@ def test_fp16_inputs(oracle, case):
     parity.compare(qr, kr, vr, tau, bm, bn, True, out, st.skip_mask)
     with pytest.raises(TypeError):
         binding.bsfa_forward(qd, kd.to(torch.bfloat16), vd, neg, block_m=bm, block_n=bn)
+
+
+def test_forward_in_a_hip_graph(oracle):
+    """bsfa_forward only enqueues kernels (the counters are cleared by a fill kernel, not a
+    memset), so it can be captured: a captured launch is replayed three times on changing inputs,
+    with eager work and synchronisation in between, and every replay must equal the eager result
+    bit for bit."""
+    shp = synth.Shape(1, 1024, 4, 2, 128, 128, 64)
+    sets = [to_dev(*synth.tiny(100 + s, shp, n_boost=5)) for s in range(3)]
+    q, k, v = (t.clone() for t in sets[0])
+    tau = binding.bsfa_calibrate(q, k, [0.5])[0].to(DEV)
+    out = torch.empty_like(q)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        binding.bsfa_forward(q, k, v, tau, out=out, skip_stats=st)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.bsfa_forward(q, k, v, tau, out=out, skip_stats=st)
+    for n, (qs, ks, vs) in enumerate(sets[::-1] + sets):
+        q.copy_(qs); k.copy_(ks); v.copy_(vs)
+        out.fill_(float("nan")); st.counts.fill_(-1); st.skip_mask.fill_(-1)
+        g.replay()
+        torch.cuda.synchronize()
+        got, got_counts, got_mask = out.clone(), st.counts.clone(), st.skip_mask.clone()
+        st2 = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+        ref = binding.bsfa_forward(qs, ks, vs, tau, skip_stats=st2)
+        torch.cuda.synchronize()
+        assert torch.equal(got, ref), "replay %d differs from the eager launch" % n
+        assert torch.equal(got_counts, st2.counts) and torch.equal(got_mask, st2.skip_mask)
+    parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask)
