@@ -523,7 +523,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // head-dim block x = n % DB), read PD MFMAs ahead
     // `mid` runs after the first PV_MID MFMAs have been issued (work that only has to happen
     // soon after the barrier goes there, beside the matrix pipe instead of in front of it)
-    constexpr int PV_MID = 4;
+    constexpr int PV_MID = 6;
     auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt, auto mid) {
         const uint32_t vaddr = vt + va_base;
         auto v_operand = [&](int n) {
