@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--seqlen", type=int, default=131072)
     ap.add_argument("--skip", type=float, default=0.5, help="target skip fraction of gateable tiles")
     ap.add_argument("--block-m", type=int, default=128)
+    ap.add_argument("--sweep", default="", help="comma-separated extra skip targets, e.g. 0.25,0.75,0.9: adds a "
+                                                "'sweep' list (time, measured skip, speed-up, eta per target) to the JSON line")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--cpu-items", type=int, default=0, help="oracle sample size (0 = sized for ~20 s)")
     ap.add_argument("--traffic-json", default=None, help="file with measured HBM bytes per launch (from rocprofv3 --pmc)")
@@ -63,7 +65,9 @@ def main():
                      dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    tau = binding.bsfa_calibrate(qc, kc, [args.skip], block_m=bm, block_n=bn, workspace=ws)[0]
+    sweep_targets = [float(x) for x in args.sweep.split(",") if x]
+    taus = binding.bsfa_calibrate(qc, kc, [args.skip] + sweep_targets, block_m=bm, block_n=bn, workspace=ws)
+    tau = taus[0]
     t_calib = time.perf_counter() - t0
     del qc, kc, ws
     torch.cuda.empty_cache()
@@ -141,17 +145,28 @@ def main():
                      "flops_per_launch": f_exec_sparse, "kernel_ms": round(kern_ms_sparse, 3)},
     }
 
+    if sweep_targets:
+        sweep = []
+        for f_t, t_l in zip(sweep_targets, taus[1:]):
+            ms_l, _, c_l = timed(t_l.to(dev), max(3, args.steps // 2), 1)
+            f_l = float(c_l[..., 0].sum()) / float(c_l[..., 2].sum())
+            sweep.append({"target_skip": f_t, "skip_fraction_of_reachable": round(f_l, 4), "ms_per_step": round(ms_l, 3),
+                          "dense_equiv_tflops": round(f_dense_equiv / (ms_l * 1e-3) / 1e12, 2),
+                          "speedup_vs_own_dense": round(ms_dense / ms_l, 4), "ideal_speedup": round(2 / (2 - f_l), 4),
+                          "skip_efficiency_eta": round((1.0 - ms_l / ms_dense) / (f_l / 2.0), 4) if f_l > 0 else None})
+        result["sweep"] = sweep
+
     if not args.no_cpu:
         from oracle import bsfa_oracle as orc
         from tests import parity
         orc.build()
         # bounded sample of (head, query tile) items of the same workload, ~20 s of oracle time
-        items = parity.sample_items(shp, n_random=3, seed=0)
+        items = parity.sample_items(shp, n_random=8, seed=0)
         if args.cpu_items:
             items = items[:args.cpu_items]
         else:
             # oracle cost grows with the tile index; cap the summed reachable key blocks
-            budget = 6e5
+            budget = 1.2e6
             keep, tot = [], 0
             for it in sorted(items, key=lambda x: x[2]):
                 nb = -(-((it[2] + 1) * bm) // bn)
