@@ -147,3 +147,25 @@ def test_longer_than_calibrated_and_ragged_64k():
     # thresholds transfer across prompts and lengths only approximately; the retained count stays
     # within a factor of a few of k and far below the ~1000 available blocks
     assert kk / 4 <= np.median(late) <= kk * 4
+
+
+def test_sampled_parity_at_256k():
+    """Twice the longest length the paper reports (64-bit addressing, 2048 query tiles per head):
+    thresholds calibrated on a second seed, three sampled (head, query tile) items against the
+    oracle, counts against the closed form."""
+    n = 262144
+    shp, (qc, kc, _) = gen(n, 1)
+    tau = binding.bsfa_calibrate(qc, kc, [0.5])[0]
+    del qc, kc
+    torch.cuda.empty_cache()
+    shp, (q, k, v) = gen(n, 0)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=st)
+    torch.cuda.synchronize()
+    c = st.counts.cpu().numpy()[0]
+    assert (c[:, 2] == shp.m_q * (shp.m_q + 1)).all() and (c[:, 1] == shp.m_q * (shp.m_q - 1)).all()
+    assert abs(c[:, 0].sum() / c[:, 1].sum() - 0.5) < 0.05
+    items = [(0, 5, 0), (0, 18, 1023), (0, 31, shp.m_q - 1)]
+    rep = parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask, None, items=items)
+    print("N=%d: max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips" % (n, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
+    assert rep.skipped > 0
