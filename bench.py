@@ -116,7 +116,7 @@ def main():
     eta = (1.0 - ms_sparse / ms_dense) / (f_skip / 2.0) if f_skip > 0 else None
 
     # HBM bytes per launch of the gated kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-    # scaled by a known-size copy (see profiles/); read from a file written from those runs
+    # scaled by a known-size copy; read from the file written from those runs
     traffic = None
     tj = args.traffic_json or os.path.join(ROOT, "profiles", "bsfa_fwd_kernel_traffic.json")
     if os.path.exists(tj):

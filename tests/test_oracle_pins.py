@@ -50,7 +50,7 @@ def expand_blocks(keep_blocks, bm, bn):
 
 CASES = [
     # (B, N, Hq, Hkv, d, BM, BN)
-    (1, 512, 2, 2, 64, 64, 64),       # BASELINE config 1 shape
+    (1, 512, 2, 2, 64, 64, 64),       # the small fp32-stated configuration: 2 heads, d=64, 64x64 tiles
     (2, 256, 4, 2, 32, 128, 64),      # the paper's tile shape, GQA 2:1, batch 2
     (1, 192, 4, 1, 16, 32, 64),       # B_M < B_N, GQA 4:1
 ]
