@@ -1,8 +1,8 @@
-// Block-Sparse FlashAttention forward kernel for gfx950 (MI355X), wave64, bf16 MFMA.
+// Block-Sparse FlashAttention forward kernel for gfx950 (MI355X), wave64, bf16 or fp16 MFMA.
 //
 // One workgroup = one query tile Q_i (B_M = 32 * NWH rows, NWH waves of 32 rows) of HP query heads
 // that share a KV head (GQA); it walks the reachable key blocks j in ascending order (Algorithm 1):
-//   S_ij^T = K_j Q_i^T        32x32x16 bf16 MFMA, fp32 accumulate                 (Eq. 5)
+//   S_ij^T = K_j Q_i^T        32x32x16 MFMA, fp32 accumulate                      (Eq. 5)
 //   s_max  = max S_ij         lane max -> wave max -> cross-wave max through LDS   (Eq. 6)
 //   gate   : s_max / sqrt(d) >= T keeps the block; blocks touching the causal boundary bypass
 //            the gate (Section 4.1).  One decision per (head, query tile, key block).
@@ -15,11 +15,11 @@
 //
 // Software pipeline, one barrier per key block.  The scores of block j+1 are computed while block
 // j is finished, so the gate decision is known one block ahead:
-//   stage j:  softmax(S_j) -> P_j          (VALU)
-//             S_{j+1} = K_{j+1} Q^T        (MFMA), block max of S_{j+1} -> LDS
+//   stage j:  softmax(S_j) -> P_j          (VALU) interleaved with
+//             S_{j+1} = K_{j+1} Q^T        (MFMA); block max of S_{j+1} -> LDS
 //             wait for the copies needed next; barrier
+//             O^T += V_j^T P_j^T           (MFMA), and a few MFMAs into it:
 //             decide keep_{j+1}; request V_{j+1} (only if kept) and K_{j+KR+1}
-//             O^T += V_j^T P_j^T           (MFMA)
 // K tiles sit in a ring of KR LDS slots and are requested KR+1 blocks ahead, V tiles in two slots;
 // both go HBM -> LDS directly, and the waits are partial (vmcnt) so that only the tile needed
 // next has to have landed.
@@ -102,7 +102,9 @@ __device__ __forceinline__ uint32_t chunk_src_offset(int r, int tid, int stride_
 // Asynchronous HBM -> LDS copy of one 64 x D tile; lds_tile is the byte address of the tile's
 // slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  The tile's first
 // row is addressed through a scalar base (it is the same for the whole workgroup), each lane adds
-// its 32-bit byte offset.  Completion is tracked by vmcnt, which this kernel manages itself
+// its 32-bit byte offset (callers pass a base computed from workgroup-uniform values only; a base
+// the compiler cannot prove uniform is rejected at build time, the asm operand being a scalar pair).
+// Completion is tracked by vmcnt, which this kernel manages itself
 // (wait_vmcnt): the instruction is emitted through inline asm so that the compiler does not
 // serialise every later LDS read behind all copies in flight.
 template <int D, int NT>
