@@ -83,6 +83,12 @@ typedef struct {
                                      beyond seqlens[b] are left untouched, query tiles beyond it
                                      get NaN block maxima, an empty skip mask and add nothing to
                                      counts. */
+    int32_t single_head_groups;   /* optional tuning knob, 0 by default: workgroups handle two query heads
+                                     of a GQA group together when the group size is even (one K/V
+                                     stream in LDS feeds both; fastest on the dense path and up to ~50 %
+                                     skip).  1: one query head per workgroup — the heads' skip decisions
+                                     no longer share a barrier, which is faster when most blocks are
+                                     skipped.  Results are identical either way. */
 } bsfa_problem;
 
 /* Optional outputs of bsfa_forward; any member may be NULL.  All DEVICE, caller allocated.

@@ -42,7 +42,8 @@ class bsfa_problem(ctypes.Structure):
                 ("q_stride_b", "q_stride_n", "q_stride_h", "k_stride_b", "k_stride_n", "k_stride_h",
                  "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
                [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32),
-                ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p)]
+                ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p),
+                ("single_head_groups", ctypes.c_int32)]
 
 
 class bsfa_skip_stats(ctypes.Structure):
@@ -94,7 +95,7 @@ def _check(status: int):
 
 def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], out: Optional[torch.Tensor],
                  block_m: int, block_n: int, thresholds_per_tile: bool = False, threshold_tiles: int = 0,
-                 seqlens: Optional[torch.Tensor] = None) -> bsfa_problem:
+                 seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False) -> bsfa_problem:
     """Descriptor for [B, N, H, d] views (any strides with a contiguous last dimension)."""
     B, N, Hq, d = q.shape
     p = bsfa_problem()
@@ -109,6 +110,7 @@ def make_problem(q: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], ou
     p.dtype = DTYPES[q.dtype]
     p.thresholds_per_tile = int(thresholds_per_tile)
     p.threshold_tiles = int(threshold_tiles)
+    p.single_head_groups = int(bool(single_head_groups))
     if seqlens is not None:
         if seqlens.dtype != torch.int32 or not seqlens.is_contiguous() or tuple(seqlens.shape) != (B,) or not seqlens.is_cuda:
             raise TypeError("bsfa: seqlens must be a contiguous int32 GPU tensor of shape [batch]")
@@ -155,7 +157,7 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
                  causal: bool = True, out: Optional[torch.Tensor] = None,
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
                  stream: Optional[torch.cuda.Stream] = None,
-                 seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False) -> torch.Tensor:
     """out = block-sparse attention of bf16 (or fp16) q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
     GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
     GPU tensor [B], causal only) gives each batch element its own length.  Enqueues on
@@ -170,7 +172,8 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
         raise ValueError("bsfa_forward: thresholds shape %s, expected [Hq] or [Hq, tiles]" % (tuple(thresholds.shape),))
     if out is None:
         out = torch.empty_like(q)
-    p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens)
+    p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens,
+                     single_head_groups)
     st = None
     if skip_stats is not None:
         st = bsfa_skip_stats(

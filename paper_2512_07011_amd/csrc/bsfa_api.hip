@@ -52,6 +52,7 @@ bsfa_status check_problem(const bsfa_problem *p, int causal)
     if (p->thresholds_per_tile != 0 && p->thresholds_per_tile != 1)
         return fail(BSFA_ERR_SHAPE, "thresholds_per_tile must be 0 or 1");
     if (p->threshold_tiles < 0) return fail(BSFA_ERR_SHAPE, "threshold_tiles must not be negative");
+    if (p->single_head_groups != 0 && p->single_head_groups != 1) return fail(BSFA_ERR_SHAPE, "single_head_groups must be 0 or 1");
     return BSFA_OK;
 }
 
@@ -72,6 +73,7 @@ void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
     fp.mask_words = (fp.mkv + 31) / 32;
     fp.causal = causal ? 1 : 0;
     fp.f16 = (p->dtype == BSFA_FP16) ? 1 : 0;
+    fp.single_head = p->single_head_groups ? 1 : 0;
     fp.tau_per_tile = p->thresholds_per_tile;
     fp.scale = 1.0f / sqrtf((float)p->head_dim);
     fp.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->head_dim));

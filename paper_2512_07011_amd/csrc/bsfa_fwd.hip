@@ -725,7 +725,7 @@ hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool ca
     if (!shape_supported(head_dim, block_m, kBlockN)) return hipErrorInvalidValue;
     // the copies address a tile with 32-bit byte offsets
     if (p.ksn * 128 > 0x7fff0000LL || p.vsn * 128 > 0x7fff0000LL) return hipErrorInvalidValue;
-    const bool pair_heads = (p.group % 2 == 0);
+    const bool pair_heads = (p.group % 2 == 0) && !p.single_head;
 #define BSFA_CASE(DD, NN, HH, KK) \
     if (head_dim == DD && block_m == 32 * NN) return launch_t<DD, NN, HH, KK>(p, calib, stream);
     if (pair_heads) {

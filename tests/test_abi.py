@@ -52,7 +52,7 @@ FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
     (dict(batch=0), -2), (dict(seqlen=0), -2), (dict(n_q_heads=3), -2), (dict(dtype=7), -3),
     (dict(head_dim=96), -4), (dict(block_m=96), -4), (dict(block_n=32), -4), (dict(block_m=256), -4),
     (dict(q_stride_n=516), -2), (dict(k_stride_h=64), -2), (dict(thresholds_per_tile=2), -2),
-    (dict(o_stride_b=-8), -2), (dict(threshold_tiles=-1), -2), (dict(seqlens=0x1002), -2),
+    (dict(o_stride_b=-8), -2), (dict(threshold_tiles=-1), -2), (dict(seqlens=0x1002), -2), (dict(single_head_groups=2), -2),
 ])
 def test_forward_rejects_bad_problems(lib, kw, code):
     p = good_problem(**kw)

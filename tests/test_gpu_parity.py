@@ -264,3 +264,21 @@ def test_forward_in_a_hip_graph(oracle):
         assert torch.equal(got, ref), "replay %d differs from the eager launch" % n
         assert torch.equal(got_counts, st2.counts) and torch.equal(got_mask, st2.skip_mask)
     parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask)
+
+
+def test_single_head_groups_gives_identical_results(oracle):
+    """The tuning knob that stops pairing the heads of a GQA group changes the schedule, not the
+    arithmetic: outputs, masks and counts are bit-identical, and both match the oracle."""
+    shp = synth.Shape(1, 1024, 8, 2, 128, 128, 64)
+    q, k, v = to_dev(*synth.tiny(71, shp, n_boost=5))
+    tau = binding.bsfa_calibrate(q, k, [0.6])[0].to(DEV)
+    res = []
+    for single in (False, True):
+        st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True, block_max=True, lse=True)
+        out = binding.bsfa_forward(q, k, v, tau, skip_stats=st, single_head_groups=single)
+        torch.cuda.synchronize()
+        res.append((out, st))
+    (o0, s0), (o1, s1) = res
+    assert torch.equal(o0, o1) and torch.equal(s0.skip_mask, s1.skip_mask) and torch.equal(s0.counts, s1.counts)
+    assert torch.equal(s0.lse, s1.lse) and torch.equal(torch.nan_to_num(s0.block_max), torch.nan_to_num(s1.block_max))
+    parity.compare(q, k, v, tau, 128, 64, True, o1, s1.skip_mask, s1.block_max, lse_gpu=s1.lse)
