@@ -39,9 +39,13 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (plain -O2, OpenMP over independent query tiles)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11",
-                               "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
+        try:
+            subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11",
+                                   "-o", tmp, _SRC, "-lm"])
+            os.replace(tmp, _LIB)
+        finally:
+            if os.path.exists(tmp):
+                os.remove(tmp)
     return _LIB
 
 

@@ -21,15 +21,17 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
     cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "is not a recognized feature for this target" not in l)
-    if r.returncode != 0:
+    try:
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in r.stdout.splitlines() if "is not a recognized feature for this target" not in l)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+        if verbose and out.strip():
+            print(out)
+        os.replace(tmp, LIB)
+    finally:                      # an interrupted or failed build leaves no partial library behind
         if os.path.exists(tmp):
             os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
-    os.replace(tmp, LIB)
     return LIB
 
 

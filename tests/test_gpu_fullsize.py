@@ -34,6 +34,14 @@ def test_sampled_parity_at_half_skip(n):
     print("N=%d: %d items, max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips"
           % (n, rep.n_items, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
     assert rep.skipped > 0
+    # the dense path (T = -inf) of the same launch configuration, on the same sampled items
+    neg = torch.full((shp.n_q_heads,), float("-inf"))
+    out = binding.bsfa_forward(q, k, v, neg.to(DEV), skip_stats=st)
+    torch.cuda.synchronize()
+    assert (st.counts.cpu().numpy()[0][:, 0] == 0).all()
+    rep = parity.compare(q, k, v, neg, 128, 64, True, out, st.skip_mask, None, items=items)
+    print("N=%d dense: %d items, max_abs %.3g mean_abs %.3g" % (n, rep.n_items, rep.max_abs, rep.mean_abs))
+    assert rep.skipped == 0 and rep.mask_mismatch == 0
 
 
 def test_sparsity_sweep_128k():

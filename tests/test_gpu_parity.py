@@ -146,7 +146,7 @@ def test_calibrate_matches_oracle_rule_and_generalises(oracle):
     for li in (1, 2, 3, 4):
         _, s2 = run_gpu(qd, kd, vd, taus[li].to(DEV), 128, 64, dump=False)
         assert (s2.counts.cpu().numpy()[0, :, 0] == np.floor(np.float32(fr[li]) * n)).all()
-    # held-out seed: measured skip fraction tracks the target (Section 5.3 reports +-0.05)
+    # held-out seed: measured skip fraction tracks the target (Section 5.2, Robustness paragraph and Table 1: within +-0.05)
     q2, k2, v2 = to_dev(*synth.llama_layer(22, shp))
     _, s3 = run_gpu(q2, k2, v2, taus[2].to(DEV), 128, 64, dump=False)
     c = s3.counts.cpu().numpy()[0]

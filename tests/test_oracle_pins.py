@@ -401,3 +401,85 @@ def test_p12_thresholds_beyond_calibrated_length_reuse_last(oracle):
     assert ((r.cls == oracle.CLS_SKIPPED) == expect).all() and expect.any()
     ref, _, _ = ragged_reference(q, k, v, used, bm, bn)
     assert np.abs(r.out - ref).max() < 2e-6
+
+
+# ---- bidirectional gate (Section 4.3, last sentence) and top-k averaged over samples (Section 4.2) ----
+@pytest.mark.parametrize("case", CASES)
+def test_p13_noncausal_gate_split_and_output_from_the_full_matrix(oracle, case):
+    """causal = 0 with finite thresholds: the blocks that overlap the tile's own token range are
+    always kept, every other block is gated on its maximum.  Classes, maxima, kept set and
+    output are recomputed here from the unmasked N x N matrix with explicit token ranges."""
+    shp, q, k, v = make(case, seed=41)
+    bm, bn, Hq = shp.block_m, shp.block_n, shp.n_q_heads
+    S = brute_scores(q, k, causal=False)
+    bmax_ref = block_view(S, bm, bn).max(axis=(3, 5))                   # [B,H,MQ,MKV]
+    own = np.zeros((shp.m_q, shp.m_kv), bool)
+    for i in range(shp.m_q):
+        rows = set(range(i * bm, (i + 1) * bm))
+        for j in range(shp.m_kv):
+            own[i, j] = bool(rows & set(range(j * bn, (j + 1) * bn)))     # shares a token index with the tile
+    assert own.sum(1).min() >= 1 and (~own).any()
+    assert (oracle.gateable_mask(shp.seqlen, bm, bn, causal=False) == ~own).all()
+    dense = oracle.forward(q, k, v, np.full(Hq, -np.inf, np.float32), bm, bn, causal=False)
+    assert ((dense.cls == oracle.CLS_DIAGONAL) == own[None, None]).all()
+    assert (dense.cls != oracle.CLS_UNREACHABLE).all() and (dense.cls != oracle.CLS_SKIPPED).all()
+    gate = np.broadcast_to(~own, bmax_ref.shape)
+    assert np.isnan(dense.bmax[~gate]).all()
+    np.testing.assert_allclose(dense.bmax[gate], bmax_ref[gate], rtol=0, atol=1e-6)
+    # per-head thresholds at the 40 % order statistic of the head's gateable maxima
+    tau = np.array([np.sort(bmax_ref[:, h][gate[:, h]].astype(np.float32))[int(0.4 * gate[:, h].sum())]
+                    for h in range(Hq)], np.float32)
+    r = oracle.forward(q, k, v, tau, bm, bn, causal=False)
+    skipped = gate & (bmax_ref.astype(np.float32) < tau[None, :, None, None])
+    assert 0 < skipped.sum() < gate.sum()
+    assert ((r.cls == oracle.CLS_SKIPPED) == skipped).all()
+    assert ((r.cls == oracle.CLS_DIAGONAL) == own[None, None]).all()
+    assert (r.counts[..., 0] == skipped.sum(axis=(2, 3))).all()
+    assert (r.counts[..., 1] == (~own).sum()).all() and (r.counts[..., 2] == own.size).all()
+    ref, _ = brute_attention(q, k, v, causal=False, key_keep=expand_blocks(~skipped, bm, bn))
+    assert np.abs(r.out - ref).max() < 2e-6
+    assert np.abs(r.psum - 1.0).max() < 1e-12
+    # +inf keeps exactly the own-range blocks
+    r = oracle.forward(q, k, v, np.full(Hq, np.inf, np.float32), bm, bn, causal=False)
+    ref, _ = brute_attention(q, k, v, causal=False, key_keep=expand_blocks(np.broadcast_to(own, gate.shape), bm, bn))
+    assert np.abs(r.out - ref).max() < 2e-6
+
+
+def test_p14_topk_thresholds_are_the_mean_over_samples(oracle):
+    """Three calibration samples: per (head, tile) the k-th largest gateable block maximum of
+    each sample, taken here from the N x N matrices with a plain sort, then numpy's mean; -inf
+    (tile has at most k gateable blocks) and +inf (k = 0) sit in the same places."""
+    shp = synth.Shape(1, 1024, 4, 2, 16, 128, 64)
+    bm, bn, Hq = 128, 64, 4
+    samples, per_sample = [], []
+    ks = [0, 1, 3, 5, 40]
+    for seed in (51, 52, 53):
+        q, k, v = synth.tiny(seed, shp, n_boost=4)
+        S = brute_scores(q.numpy(), k.numpy())
+        blk = block_view(S, bm, bn)
+        full = np.isfinite(blk).all(axis=(3, 5))[0, 0]                # [MQ,MKV] gateable = nothing masked
+        bmax = blk.max(axis=(3, 5))[0].astype(np.float32)              # [Hq,MQ,MKV]
+        samples.append(np.where(full[None], bmax, np.nan))
+        T = np.empty((len(ks), Hq, shp.m_q), np.float64)
+        for h in range(Hq):
+            for i in range(shp.m_q):
+                x = np.sort(bmax[h, i][full[i]])[::-1]
+                for li, kk in enumerate(ks):
+                    T[li, h, i] = np.inf if kk == 0 and x.size > 0 else (-np.inf if x.size <= kk else x[kk - 1])
+        per_sample.append(T)
+    gate = oracle.gateable_mask(1024, bm, bn)
+    assert (gate == full).all()
+    got = oracle.calibrate_topk(samples, gate, ks)
+    with np.errstate(invalid="ignore"):
+        want = np.mean(np.stack(per_sample), axis=0)
+    assert (np.isinf(got) == np.isinf(want)).all() and (np.sign(got[np.isinf(got)]) == np.sign(want[np.isinf(want)])).all()
+    fin = np.isfinite(want)
+    assert fin.any() and np.isinf(want).any()
+    np.testing.assert_allclose(got[fin], want[fin].astype(np.float32), rtol=2e-7, atol=0)
+    # the three samples differ, so the mean differs from every single-sample result
+    for T in per_sample:
+        assert np.abs(T[fin] - want[fin]).max() > 1e-3
+    # one sample is its own mean
+    one = oracle.calibrate_topk(samples[:1], gate, ks)
+    f1 = np.isfinite(per_sample[0])
+    np.testing.assert_array_equal(one[f1], per_sample[0][f1].astype(np.float32))
