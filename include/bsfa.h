@@ -89,6 +89,14 @@ typedef struct {
                                      skip).  1: one query head per workgroup — the heads' skip decisions
                                      no longer share a barrier, which is faster when most blocks are
                                      skipped.  Results are identical either way. */
+    void   *workspace;            /* optional, DEVICE, 256-byte aligned, bsfa_forward only: scratch memory of at
+                                     least bsfa_forward_workspace_bytes() bytes, overwritten by every call.
+                                     With it (and block_m = 128) the forward pass first rewrites V, once, as
+                                     transposed 64-key tiles (an O(N) pass: 2 x the size of V in traffic) so
+                                     that the second matrix product reads its V operand from on-chip memory
+                                     with full-width reads; the per-(tile, block) V loads stay conditional on
+                                     the gate.  NULL: V is read in place.  Results are identical either way. */
+    int64_t workspace_bytes;      /* size of workspace in bytes */
 } bsfa_problem;
 
 /* Optional outputs of bsfa_forward; any member may be NULL.  All DEVICE, caller allocated.
@@ -121,6 +129,10 @@ typedef struct {
 bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, const void *v,
                          const float *thresholds, int causal, void *out,
                          const bsfa_skip_stats *skip_stats /* may be NULL */, void *hip_stream);
+
+/* Bytes of workspace bsfa_forward can use for *p (size of V rounded up to whole 64-key blocks, plus
+ * alignment slack); 0 if *p is invalid or its tile shape makes no use of a workspace. */
+size_t bsfa_forward_workspace_bytes(const bsfa_problem *p);
 
 /*
  * Calibration of per-head thresholds (Section 4.2 reduced over query positions): runs the

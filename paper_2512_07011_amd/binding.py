@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libbsfa.so")
 BSFA_OK = 0
 STATUS_NAMES = {0: "BSFA_OK", -1: "BSFA_ERR_NULL", -2: "BSFA_ERR_SHAPE", -3: "BSFA_ERR_DTYPE",
                 -4: "BSFA_ERR_UNSUPPORTED", -5: "BSFA_ERR_WORKSPACE", -6: "BSFA_ERR_HIP"}
-EXPORTS = ["bsfa_forward", "bsfa_calibrate", "bsfa_calibrate_topk", "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
+EXPORTS = ["bsfa_forward", "bsfa_forward_workspace_bytes", "bsfa_calibrate", "bsfa_calibrate_topk",
+           "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
            "bsfa_status_string", "bsfa_last_error"]
 
 
@@ -43,7 +44,8 @@ class bsfa_problem(ctypes.Structure):
                  "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
                [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32),
                 ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p),
-                ("single_head_groups", ctypes.c_int32)]
+                ("single_head_groups", ctypes.c_int32), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_int64)]
 
 
 class bsfa_skip_stats(ctypes.Structure):
@@ -77,6 +79,8 @@ def lib() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
         L.bsfa_calibrate_workspace_bytes.restype = ctypes.c_size_t
         L.bsfa_calibrate_workspace_bytes.argtypes = [ctypes.POINTER(bsfa_problem)]
+        L.bsfa_forward_workspace_bytes.restype = ctypes.c_size_t
+        L.bsfa_forward_workspace_bytes.argtypes = [ctypes.POINTER(bsfa_problem)]
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.bsfa_query_build.restype = ctypes.c_int
         L.bsfa_query_build.argtypes = [i32p, i32p, i32p, ctypes.c_int]
@@ -147,6 +151,26 @@ def alloc_stats(q: torch.Tensor, block_m: int, block_n: int, counts=True, skip_m
     return s
 
 
+_workspaces = {}
+
+
+def _cached_workspace(device, nbytes: int):
+    """One growing scratch tensor per device for callers that do not manage the forward workspace
+    themselves (calls that overlap on different streams must pass their own)."""
+    if nbytes == 0:
+        return None
+    w = _workspaces.get(device)
+    if w is None or w.numel() < nbytes:
+        w = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _workspaces[device] = w
+    return w
+
+
+def forward_workspace_bytes(q: torch.Tensor, k: torch.Tensor, block_m: int = 128, block_n: int = 64) -> int:
+    """Bytes of workspace bsfa_forward can use for these shapes (0: none)."""
+    return int(lib().bsfa_forward_workspace_bytes(ctypes.byref(make_problem(q, k, None, None, block_m, block_n))))
+
+
 def _dev_check(*ts):
     for t in ts:
         if t is not None and not t.is_cuda:
@@ -157,11 +181,14 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
                  causal: bool = True, out: Optional[torch.Tensor] = None,
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
                  stream: Optional[torch.cuda.Stream] = None,
-                 seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False) -> torch.Tensor:
+                 seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False,
+                 workspace=True) -> torch.Tensor:
     """out = block-sparse attention of bf16 (or fp16) q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
     GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
-    GPU tensor [B], causal only) gives each batch element its own length.  Enqueues on
-    ``stream`` (default: torch's current stream)."""
+    GPU tensor [B], causal only) gives each batch element its own length.  ``workspace``: a uint8
+    GPU tensor of at least forward_workspace_bytes(...) bytes, True (a cached tensor per device is
+    used) or False/None (no workspace: V is read in place).  Enqueues on ``stream`` (default:
+    torch's current stream)."""
     _dev_check(q, k, v, thresholds, out)
     _same_16bit("bsfa_forward", q, k, v, *([out] if out is not None else []))
     if thresholds.dtype != torch.float32 or not thresholds.is_contiguous():
@@ -174,6 +201,12 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
         out = torch.empty_like(q)
     p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens,
                      single_head_groups)
+    if workspace is True:
+        workspace = _cached_workspace(q.device, lib().bsfa_forward_workspace_bytes(ctypes.byref(p)))
+    if workspace is not None and workspace is not False:
+        _dev_check(workspace)
+        p.workspace = workspace.data_ptr()
+        p.workspace_bytes = workspace.numel() * workspace.element_size()
     st = None
     if skip_stats is not None:
         st = bsfa_skip_stats(

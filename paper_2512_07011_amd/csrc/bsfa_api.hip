@@ -53,6 +53,7 @@ bsfa_status check_problem(const bsfa_problem *p, int causal)
         return fail(BSFA_ERR_SHAPE, "thresholds_per_tile must be 0 or 1");
     if (p->threshold_tiles < 0) return fail(BSFA_ERR_SHAPE, "threshold_tiles must not be negative");
     if (p->single_head_groups != 0 && p->single_head_groups != 1) return fail(BSFA_ERR_SHAPE, "single_head_groups must be 0 or 1");
+    if (p->workspace_bytes < 0) return fail(BSFA_ERR_WORKSPACE, "workspace_bytes must not be negative");
     return BSFA_OK;
 }
 
@@ -99,6 +100,14 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
     fp.v = static_cast<const uint16_t *>(v);
     fp.out = static_cast<uint16_t *>(out);
     fp.tau = thresholds;
+    if (p->workspace) {
+        const size_t need = bsfa_forward_workspace_bytes(p);
+        if (need) {                   // (tile shapes that take V in place ignore the workspace)
+            if ((size_t)p->workspace_bytes < need)
+                return fail(BSFA_ERR_WORKSPACE, "forward workspace of %zu bytes needed, %lld given", need, (long long)p->workspace_bytes);
+            fp.vt = reinterpret_cast<uint16_t *>((reinterpret_cast<uintptr_t>(p->workspace) + 255) & ~(uintptr_t)255);
+        }
+    }
     if (skip_stats) {
         fp.counts = reinterpret_cast<unsigned long long *>(skip_stats->counts);
         fp.skip_mask = skip_stats->skip_mask;
@@ -108,6 +117,13 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
     hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, false, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(BSFA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
     return BSFA_OK;
+}
+
+size_t bsfa_forward_workspace_bytes(const bsfa_problem *p)
+{
+    if (check_problem(p, 1) != BSFA_OK || p->block_m != 128) return 0;
+    const size_t mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
+    return (size_t)p->batch * p->n_kv_heads * mkv * (size_t)p->block_n * p->head_dim * 2 + 256;
 }
 
 size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)

@@ -23,196 +23,9 @@
 // K tiles sit in a ring of KR LDS slots and are requested KR+1 blocks ahead, V tiles in two slots;
 // both go HBM -> LDS directly, and the waits are partial (vmcnt) so that only the tile needed
 // next has to have landed.
-#include "bsfa_internal.h"
-
-#include <math.h>
-
-#include <type_traits>
+#include "bsfa_dev.h"
 
 namespace bsfa {
-
-// The 16-bit element type of Q, K, V, P and O: bf16 or fp16 (the paper's kernel is fp16
-// throughout, Section 5.1).  Same storage size, same MFMA shape, same LDS layout; only the
-// matrix instruction, the pack and the pair sum differ.
-template <bool F16> struct Elem;
-template <> struct Elem<false> {
-    typedef __bf16 T;
-    typedef __bf16 x8 __attribute__((ext_vector_type(8)));
-    typedef __bf16 x4 __attribute__((ext_vector_type(4)));
-    typedef __bf16 x2 __attribute__((ext_vector_type(2)));
-};
-template <> struct Elem<true> {
-    typedef _Float16 T;
-    typedef _Float16 x8 __attribute__((ext_vector_type(8)));
-    typedef _Float16 x4 __attribute__((ext_vector_type(4)));
-    typedef _Float16 x2 __attribute__((ext_vector_type(2)));
-};
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
-// 32x32x16 MFMA, fp32 accumulate, and p0 + p1 + acc on a packed pair: one overload per element type
-__device__ __forceinline__ f32x16 mfma16(bf16x8_t a, bf16x8_t b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-__device__ __forceinline__ f32x16 mfma16(f16x8_t a, f16x8_t b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
-__device__ __forceinline__ float pair_sum(bf16x2_t pp, float acc)
-{
-    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
-    return __builtin_amdgcn_fdot2_f32_bf16(pp, ones, acc, false);
-}
-__device__ __forceinline__ float pair_sum(f16x2_t pp, float acc)
-{
-    const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
-    return __builtin_amdgcn_fdot2(pp, ones, acc, false);
-}
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(uintptr_t)(p))
-#define GLB_PTR(T, p) ((const __attribute__((address_space(1))) T *)(p))
-
-// ---- LDS tile layout --------------------------------------------------------------------
-// A K or V tile is 64 rows x D bf16, stored as 16-byte chunks, row-major, the chunk index
-// XOR-ed with a function of the row so that the operand gathers spread over the banks.  The
-// swizzle is applied on the global side of the copy (lane -> which chunk it fetches); the LDS
-// side of a direct copy is always linear (wave base + lane * 16 bytes).  Both swizzles only
-// touch chunk bits that the gather loops step through with XOR-able constants, so every
-// operand address is  (per-lane base) ^ (loop constant) + (immediate offset).
-template <int D> __device__ __forceinline__ int swz_k(int row)
-{
-    return (D == 128) ? (row & 15) : ((row >> 1) & 7);
-}
-template <int D> __device__ __forceinline__ int swz_v(int row)
-{
-    return (D == 128) ? ((row & 7) << 1) : (((row >> 1) & 3) << 1);
-}
-
-// Byte offset (relative to the tile's first row) of the chunk thread `tid` copies in
-// repetition r; rows at and beyond `rows` are fetched from row rows - 1.
-template <int D, int NT, bool ISV>
-__device__ __forceinline__ uint32_t chunk_src_offset(int r, int tid, int stride_n, int rows = 64)
-{
-    constexpr int CPR = D / 8;
-    const int sigma = r * NT + tid;
-    const int row = sigma / CPR, cp = sigma % CPR;
-    const int c = cp ^ (ISV ? swz_v<D>(row) : swz_k<D>(row));
-    return (uint32_t)(min(row, rows - 1) * stride_n + 8 * c) * 2u;
-}
-
-// Asynchronous HBM -> LDS copy of one 64 x D tile; lds_tile is the byte address of the tile's
-// slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  The tile's first
-// row is addressed through a scalar base (it is the same for the whole workgroup), each lane adds
-// its 32-bit byte offset (callers pass a base computed from workgroup-uniform values only; a base
-// the compiler cannot prove uniform is rejected at build time, the asm operand being a scalar pair).
-// Completion is tracked by vmcnt, which this kernel manages itself
-// (wait_vmcnt): the instruction is emitted through inline asm so that the compiler does not
-// serialise every later LDS read behind all copies in flight.
-template <int D, int NT>
-__device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const uint32_t (&off)[64 * (D / 8) / NT],
-                                                uint32_t lds_tile, int wave)
-{
-#pragma unroll
-    for (int r = 0; r < 64 * (D / 8) / NT; ++r) {
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :
-                     : "s"(dst), "v"(off[r]), "s"(gtile)
-                     : "memory");
-    }
-}
-
-// The same copy for the last key block of a sequence that does not fill it: rows at and beyond
-// `rows` are fetched from row rows-1, which is the repeat-last-token padding of Section 4.3
-// (and keeps the copy inside the caller's buffers).  Same number of requests per lane as
-// tile_copy_async, so the vmcnt bookkeeping does not change.  The offsets are computed here, at
-// the one place per sequence that needs them, from the lane id (no long-lived registers).
-template <int D, int NT, bool ISV>
-__device__ __forceinline__ void tile_copy_async_clamped(const uint16_t *gtile, int stride_n, int rows,
-                                                        uint32_t lds_tile, int wave)
-{
-    int tid = wave * 64 + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-    asm volatile("" : "+v"(tid));       // keeps the offsets from being hoisted out of the key loop
-    uint32_t off[64 * (D / 8) / NT];
-#pragma unroll
-    for (int r = 0; r < 64 * (D / 8) / NT; ++r) off[r] = chunk_src_offset<D, NT, ISV>(r, tid, stride_n, rows);
-    tile_copy_async<D, NT>(gtile, off, lds_tile, wave);
-}
-
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
-}
-
-// Workgroup barrier that orders LDS traffic only: the global -> LDS copies in flight are tracked
-// separately with wait_vmcnt, so the barrier must not drain them.
-__device__ __forceinline__ void wg_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// max over lanes l and l^32, result in both lanes.  v_permlane32_swap exchanges the upper half
-// of its first operand with the lower half of its second: with two copies of x the first
-// register ends up holding x[l & 31] and the second x[32 + (l & 31)] in every lane.  Written as
-// one asm block so that the two copies are guaranteed to live in different registers.
-__device__ __forceinline__ float pair_max(float x)
-{
-    float a = x, b;
-    asm volatile("v_mov_b32 %1, %0\n\ts_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
-                 : "+v"(a), "=&v"(b));
-    return a;
-}
-
-// max over the wave of a value that is already equal in lanes l and l^32 (wave-uniform result):
-// four DPP steps inside each row of 16 lanes, then rows 0 and 1 are combined through SGPRs.
-__device__ __forceinline__ float wave_max_paired(float x)
-{
-    asm volatile("s_nop 1\n\t"
-                 "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
-                 "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
-                 "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
-                 "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1"
-                 : "+v"(x));
-    const int xi = __builtin_bit_cast(int, x);
-    return fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)),
-                 __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)));
-}
-
-// Work decomposition: a work item is (batch b, KV head, group of HP query heads, query tile i).
-// With at least 8 (batch, KV head) pairs the pair is chosen by the low three bits of the
-// workgroup id, which is the XCD the hardware dispatches the group to, so that all groups
-// streaming one K/V sequence share one L2.  Heavy (late) query tiles first.
-template <int HP>
-__device__ __forceinline__ bool decode_work(const FwdParams &p, int w, int &b, int &h0, int &i)
-{
-    const int pairs = p.batch * p.hkv;
-    const int gsub = p.group / HP;               // head groups per KV head
-    int pair, hg, idesc;
-    if (pairs >= 8) {
-        const int x = w & 7, r = w >> 3;
-        const int npx = (pairs + 7) >> 3;
-        const int per_tile = npx * gsub;
-        idesc = r / per_tile;
-        const int rest = r - idesc * per_tile;
-        const int pl = rest / gsub;
-        hg = rest - pl * gsub;
-        pair = x + 8 * pl;
-        if (pair >= pairs) return false;
-    } else {
-        const int per_tile = pairs * gsub;
-        idesc = w / per_tile;
-        const int rest = w - idesc * per_tile;
-        pair = rest / gsub;
-        hg = rest - pair * gsub;
-    }
-    b = pair / p.hkv;
-    h0 = (pair - b * p.hkv) * p.group + hg * HP;
-    i = p.mq - 1 - idesc;
-    return true;
-}
 
 struct ScoreTile {
     f32x16 s[2];          // S^T: [32-key half], raw q.k (no 1/sqrt(d)); column = this lane's query
@@ -223,7 +36,7 @@ struct ScoreTile {
     float alpha;          // kept blocks: factor that rescales the running accumulator and normaliser
 };
 
-template <int D, int NWH, int HP, int KR, bool CALIB, bool F16>
+template <int D, int NWH, int HP, int KR, bool CALIB, bool F16, bool VT>
 __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdParams p)
 {
     typedef typename Elem<F16>::T el;                    // element type of Q, K, V, P, O
@@ -286,27 +99,30 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     const int own_lo = (int)(row0 / BN), own_hi = (int)((row0 + BM + BN - 1) / BN);
 
     const uint16_t *kbase = p.k + (int64_t)b * p.ksb + (int64_t)g * p.ksh;
-    const uint16_t *vbase = p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
+    // VT: V comes from the workspace, one pre-transposed, pre-swizzled 64-key tile after the other
+    const uint16_t *vbase = VT ? p.vt + ((int64_t)b * p.hkv + g) * p.mkv * (int64_t)(BN * D)
+                               : p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
     float tau_h[HP];                                      // thresholds of the group's heads for this tile
 #pragma unroll
     for (int x = 0; x < HP; ++x)     // tiles past the calibrated length use its last tile's threshold (Section 4.3)
-        tau_h[x] = p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
+        tau_h[x] = CALIB ? -INFINITY      // the score half takes no decisions
+                         : p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
 
     uint32_t koff[NST], voff[NST];
 #pragma unroll
     for (int r = 0; r < NST; ++r) {
         koff[r] = chunk_src_offset<D, NT, false>(r, tid, (int)p.ksn);
-        voff[r] = chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
+        voff[r] = VT ? (uint32_t)(r * NT + tid) * 16u : chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
     }
-    const int64_t kstep = (int64_t)BN * p.ksn, vstep = (int64_t)BN * p.vsn;
+    const int64_t kstep = (int64_t)BN * p.ksn, vstep = VT ? (int64_t)(BN * D) : (int64_t)BN * p.vsn;
     auto copy_k = [&](int t, uint32_t dst) {              // K_t into the ring slot at LDS byte address dst
         if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
         else tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
     };
     auto copy_v = [&](int t) {                            // V_t into slot t & 1
         const uint32_t dst = lds_v0 + (uint32_t)(t & 1) * TILE_BYTES;
-        if (t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave);
-        else tile_copy_async<D, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);
+        if (!VT && t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave);
+        else tile_copy_async<D, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);   // (workspace tiles are padded already)
     };
 
     // Operand gather addresses (bytes inside a tile slot).
@@ -328,7 +144,13 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     const int L = lane & 15, g16 = (lane >> 4) & 1;
     const int vrow = 4 * hh + (L >> 2);
     const int vcol = G16_COLS * g16 + 4 * (L & 3);
-    const uint32_t va_base = (uint32_t)(vrow * ROW_BYTES + (((vcol >> 3) ^ swz_v<D>(vrow)) << 4) + ((vcol >> 2) & 1) * 8);
+    // VT: the tile holds V^T, D rows of 64 keys (128 bytes), the keys of every 16-key step ordered
+    // so that the 8 keys a lane multiplies are contiguous, the 16-byte chunk index XOR-ed with
+    // (row >> 1) & 7.  Lane reads row 32x + l32, chunk 2u + hh, as one b128:
+    // addr(u, x) = (va_base ^ (u << 5)) + x * 32 * 128 -- conflict-free (16 lanes hit 16 distinct
+    // (row parity, chunk) slots), and at twice the LDS rate of the transposing reads.
+    const uint32_t va_base = VT ? (uint32_t)(l32 * 128 + ((hh ^ ((l32 >> 1) & 7)) << 4))
+                                : (uint32_t)(vrow * ROW_BYTES + (((vcol >> 3) ^ swz_v<D>(vrow)) << 4) + ((vcol >> 2) & 1) * 8);
 
     // Q_i^T as the B operand: lane holds query (32*wrow + l32), head-dim slice 16s + 8hh .. +7
     bf16x8 qreg[KS];
@@ -530,6 +352,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const uint32_t vaddr = vt + va_base;
         auto v_operand = [&](int n) {
             const int u = n / DB, x = n % DB;
+            if constexpr (VT) return *LDS_PTR(const bf16x8, (vaddr ^ (uint32_t)(u << 5)) + x * 32 * 128);
             const uint32_t a_x = (vaddr ^ (uint32_t)(x << XSH)) + u * 16 * ROW_BYTES;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a_x + 8 * ROW_BYTES));
@@ -595,6 +418,10 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         // decision for block j+1, then the requests for V_{j+1} and K_{j+R}
         auto look_ahead = [&]() {
             if (has_next) {
+                // the maxima are consumed here and not earlier: nothing computed from them may be
+                // hoisted in front of the PV MFMAs, where it would wait for the LDS read
+#pragma unroll
+                for (int w = 0; w < NW; ++w) asm volatile("" : "+v"(red[w]));
                 decide(nxt, j + 1, red, fast_tag);
                 if (!CALIB && nxt.keep) softmax_begin(nxt);   // running max and rescale factor, off the critical path
                 if (!CALIB && nxt.any_keep) {
@@ -674,7 +501,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             for (int e4 = 0; e4 < 4; ++e4) {
                 // O^T row 8*e4 + 4hh + e of block x -> head-dim column (see the V operand mapping)
                 const int m0 = 8 * e4 + 4 * hh;
-                const int d0 = X_COLS * x + (m0 < 16 ? m0 : G16_COLS + m0 - 16);
+                const int d0 = VT ? 32 * x + m0 : X_COLS * x + (m0 < 16 ? m0 : G16_COLS + m0 - 16);
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (el)(oacc[x][4 * e4 + e] * inv);
@@ -689,13 +516,53 @@ __global__ void zero_counts_kernel(unsigned long long *c, int n)
     if (t < n) c[t] = 0ull;
 }
 
-template <int D, int NWH, int HP, int KR, bool F16>
+// V -> workspace, once per forward call: for every (batch, KV head, 64-key block) the tile V_j^T in
+// exactly the byte order the forward kernel wants in LDS (see its operand addresses): D rows of 64
+// keys; inside a 16-key step the keys are ordered 0-3, 8-11, 4-7, 12-15 (the 8 keys one lane of the
+// second MFMA multiplies are then 16 contiguous bytes); the 16-byte chunk index is XOR-ed with
+// (row >> 1) & 7.  Rows at and beyond the sequence end repeat the last token (Section 4.3), so the
+// tile of a partial block holds finite values everywhere; blocks that lie entirely beyond the end
+// are never read and are not written.  One workgroup per tile, through LDS.
+template <int D>
+__global__ void __launch_bounds__(256) transpose_v_kernel(const FwdParams p)
+{
+    constexpr int BN = kBlockN, CPR = D / 8, LD = D + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t tile[BN * LD];
+    const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    int n_tok = p.seqlen;
+    if (p.seqlens) n_tok = min(max(p.seqlens[b], 0), p.seqlen);
+    if (j * BN >= n_tok) return;
+    const uint16_t *src = p.v + (int64_t)b * p.vsb + (int64_t)g * p.vsh;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    for (int sigma = tid; sigma < BN * CPR; sigma += 256) {
+        const int row = sigma / CPR, cp = sigma % CPR;
+        const int tok = min(j * BN + row, n_tok - 1);
+        const u32x4 c = *reinterpret_cast<const u32x4 *>(src + (int64_t)tok * p.vsn + 8 * cp);
+        *reinterpret_cast<u32x4 *>(&tile[row * LD + 8 * cp]) = c;
+    }
+    __syncthreads();
+    uint16_t *dst = p.vt + (((int64_t)b * p.hkv + g) * p.mkv + j) * (int64_t)(BN * D);
+    for (int sigma = tid; sigma < D * 8; sigma += 256) {
+        const int d = sigma >> 3, cphys = sigma & 7;
+        const int c = cphys ^ ((d >> 1) & 7);        // logical chunk: 16-key step c >> 1, lane half c & 1
+        const int u = c >> 1, hh = c & 1;
+        uint16_t w[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) w[t] = tile[(16 * u + 8 * (t >> 2) + 4 * hh + (t & 3)) * LD + d];
+        u32x4 o;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o[t] = (uint32_t)w[2 * t] | ((uint32_t)w[2 * t + 1] << 16);
+        *reinterpret_cast<u32x4 *>(dst + (int64_t)sigma * 8) = o;
+    }
+}
+
+template <int D, int NWH, int HP, int KR, bool F16, bool VT>
 static hipError_t launch_k(const FwdParams &p, bool calib, hipStream_t stream, long grid)
 {
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true, F16>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true, F16, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false, F16>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false, F16, VT>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -710,7 +577,16 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
-    return p.f16 ? launch_k<D, NWH, HP, KR, true>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false>(p, calib, stream, grid);
+    if constexpr (NWH == 4) {          // the 128-row tile can take V from the transposed workspace
+        if (p.vt && !calib) {
+            if (p.hkv > 65535 || p.batch > 65535) return hipErrorInvalidValue;    // grid y, z limits
+            hipLaunchKernelGGL((transpose_v_kernel<D>), dim3((unsigned)p.mkv, (unsigned)p.hkv, (unsigned)p.batch), dim3(256), 0, stream, p);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            return p.f16 ? launch_k<D, NWH, HP, KR, true, true>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, true>(p, calib, stream, grid);
+        }
+    }
+    return p.f16 ? launch_k<D, NWH, HP, KR, true, false>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, false>(p, calib, stream, grid);
 }
 
 bool shape_supported(int head_dim, int block_m, int block_n)

@@ -11,6 +11,8 @@ constexpr int kBlockN = 64;
 struct FwdParams {
     const uint16_t *q, *k, *v;       // bf16 or fp16 bit patterns (f16 says which)
     uint16_t *out;
+    uint16_t *vt;                    // workspace for the transposed V tiles ([batch][hkv][mkv] tiles of 64 x head_dim
+                                     // elements), or null: V is then gathered with transposing LDS reads
     const float *tau;                // [hq] or [hq][tau_tiles]
     const int32_t *seqlens;          // [batch] tokens per batch element, or null (all have seqlen)
     int64_t qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;

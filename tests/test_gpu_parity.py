@@ -282,3 +282,35 @@ def test_single_head_groups_gives_identical_results(oracle):
     assert torch.equal(o0, o1) and torch.equal(s0.skip_mask, s1.skip_mask) and torch.equal(s0.counts, s1.counts)
     assert torch.equal(s0.lse, s1.lse) and torch.equal(torch.nan_to_num(s0.block_max), torch.nan_to_num(s1.block_max))
     parity.compare(q, k, v, tau, 128, 64, True, o1, s1.skip_mask, s1.block_max, lse_gpu=s1.lse)
+
+
+@pytest.mark.parametrize("case,dtype", [((1, 1152, 16, 8, 128, 128, 64), torch.bfloat16), ((2, 640, 4, 2, 64, 128, 64), torch.float16),
+                                        ((1, 900, 6, 2, 128, 128, 64), torch.bfloat16)])
+def test_workspace_path_is_bit_identical_to_in_place_v(case, dtype):
+    """With a workspace V is first rewritten as transposed tiles and the second product reads it with
+    full-width LDS reads; without one V is gathered in place with transposing reads.  Both feed the
+    same numbers to the same MFMAs: outputs, masks and log-sum-exps must be equal bit for bit
+    (paired heads, single heads, ragged length, a workspace that is too small)."""
+    shp = synth.Shape(*case)
+    q, k, v = (t.to(dtype).to(DEV) for t in synth.tiny(77, shp, n_boost=max(1, shp.m_kv // 3)))
+    if case[1] == 900:
+        q, k, v = (t[:, :870].contiguous() for t in (q, k, v))
+    tau = binding.bsfa_calibrate(q, k, [0.5])[0].to(DEV)
+    need = binding.forward_workspace_bytes(q, k)
+    assert need >= v.numel() * 2
+    ws = torch.full((need + 512,), 0xFF, dtype=torch.uint8, device=DEV)       # NaN bit patterns everywhere
+    res = {}
+    for name, kw in (("in_place", dict(workspace=None)), ("workspace", dict(workspace=ws[256:])),
+                     ("workspace_single", dict(workspace=ws, single_head_groups=True)),
+                     ("in_place_single", dict(workspace=None, single_head_groups=True))):
+        st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True, lse=True)
+        out = binding.bsfa_forward(q, k, v, tau, skip_stats=st, **kw)
+        torch.cuda.synchronize()
+        res[name] = (out.clone(), st.skip_mask.clone(), st.lse.clone(), st.counts.clone())
+    assert res["in_place"][3][..., 0].sum() > 0
+    for name in ("workspace", "workspace_single", "in_place_single"):
+        for a, b in zip(res["in_place"], res[name]):
+            assert torch.equal(a, b), name
+    with pytest.raises(binding.BsfaError) as e:
+        binding.bsfa_forward(q, k, v, tau, workspace=ws[:need - 1024])
+    assert e.value.status == -5
