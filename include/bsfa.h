@@ -141,10 +141,12 @@ size_t bsfa_forward_workspace_bytes(const bsfa_problem *p);
  * r = floor(f * n), of the n block maxima of that head's gateable tiles sorted ascending
  * (-INFINITY if r == 0, +INFINITY if r == n).  With the keep rule s_max >= threshold exactly r
  * tiles of the calibration batch are skipped, absent ties.
- *   target_skip_fractions HOST [n_levels], each in [0, 1]
+ *   target_skip_fractions HOST [n_levels], each in [0, 1]; n_levels <= 64
  *   thresholds_out        HOST [n_levels][n_q_heads]
  *   workspace             DEVICE, at least bsfa_calibrate_workspace_bytes(p) bytes
- * p->thresholds_per_tile must be 0.  Synchronises hip_stream.
+ * p->thresholds_per_tile must be 0.  The selection runs on the GPU (exact order statistics by radix
+ * passes over the block maxima); only the n_levels x n_q_heads results are copied to the host.
+ * Synchronises hip_stream.
  */
 bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, int causal,
                            const float *target_skip_fractions, int n_levels,

@@ -130,7 +130,9 @@ size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
 {
     if (check_problem(p, 1) != BSFA_OK) return 0;
     const size_t mq = (size_t)((p->seqlen + p->block_m - 1) / p->block_m), mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
-    return (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float) + 256;
+    const size_t dump = (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float);
+    // block-maximum dump | selection area | per-level results, each 256-byte aligned
+    return dump + bsfa::select_area_bytes(p->n_q_heads) + (size_t)bsfa::kMaxLevels * p->n_q_heads * sizeof(float) + 4 * 256;
 }
 
 // Shared front half of the calibration entry points: checks, score / block-maximum kernel,
@@ -148,8 +150,7 @@ static bsfa_status block_maxima_to_host(const bsfa_problem *p, const void *q, co
     fp.q = static_cast<const uint16_t *>(q);
     fp.k = static_cast<const uint16_t *>(k);
     fp.block_max = reinterpret_cast<float *>((reinterpret_cast<uintptr_t>(workspace) + 255) & ~(uintptr_t)255);
-    // the score half of the kernel reads a threshold per work item but never acts on it
-    fp.tau = fp.block_max;
+    fp.tau = nullptr;                 // the score half takes no decisions and reads no thresholds
     fp.tau_per_tile = 0;
     fp.tau_tiles = 1;
     hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
@@ -161,46 +162,65 @@ static bsfa_status block_maxima_to_host(const bsfa_problem *p, const void *q, co
     return BSFA_OK;
 }
 
+// Shared body of the per-head calibration entry points: argument checks, the score / block-maximum
+// kernel into `dump`, the order statistics on the GPU into out_dev.  Everything is enqueued on the
+// stream; nothing is allocated and the host does not wait.
+static bsfa_status calibrate_on_device(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                       const float *target_skip_fractions, int n_levels,
+                                       float *dump, void *area, float *out_dev, hipStream_t stream)
+{
+    if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "per-head calibration produces per-head thresholds only");
+    if (!q || !k || !target_skip_fractions) return fail(BSFA_ERR_NULL, "q, k and fractions must be non-NULL");
+    if (!aligned16(q) || !aligned16(k)) return fail(BSFA_ERR_SHAPE, "q and k must be 16-byte aligned");
+    if (n_levels < 1 || n_levels > bsfa::kMaxLevels) return fail(BSFA_ERR_SHAPE, "n_levels must be between 1 and %d", bsfa::kMaxLevels);
+    bsfa::SelectLevels lv;
+    memset(&lv, 0, sizeof(lv));
+    for (int l = 0; l < n_levels; ++l) {
+        if (!(target_skip_fractions[l] >= 0.f && target_skip_fractions[l] <= 1.f))
+            return fail(BSFA_ERR_SHAPE, "target skip fraction #%d = %g is outside [0, 1]", l, (double)target_skip_fractions[l]);
+        lv.f[l] = target_skip_fractions[l];
+    }
+    if ((long)p->batch * p->n_q_heads > 65535) return fail(BSFA_ERR_UNSUPPORTED, "batch * n_q_heads must not exceed 65535 for calibration");
+    bsfa::FwdParams fp;
+    fill_params(fp, p, causal);
+    fp.q = static_cast<const uint16_t *>(q);
+    fp.k = static_cast<const uint16_t *>(k);
+    fp.block_max = dump;
+    fp.tau = nullptr;                 // the score half takes no decisions and reads no thresholds
+    fp.tau_per_tile = 0;
+    fp.tau_tiles = 1;
+    hipError_t e = bsfa::launch_forward(fp, p->head_dim, p->block_m, true, stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
+    e = bsfa::launch_select(dump, (long)fp.mq * fp.mkv, p->batch, p->n_q_heads, lv, n_levels, area, out_dev, stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "selection launch failed: %s", hipGetErrorString(e));
+    return BSFA_OK;
+}
+
+static uintptr_t up256(uintptr_t x) { return (x + 255) & ~(uintptr_t)255; }
+
 bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, int causal,
                            const float *target_skip_fractions, int n_levels, float *thresholds_out,
                            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     bsfa_status s = check_problem(p, causal);
     if (s != BSFA_OK) return s;
-    if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate produces per-head thresholds only");
-    if (!q || !k || !target_skip_fractions || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, fractions and thresholds_out must be non-NULL");
-    if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
-    for (int l = 0; l < n_levels; ++l)
-        if (!(target_skip_fractions[l] >= 0.f && target_skip_fractions[l] <= 1.f))
-            return fail(BSFA_ERR_SHAPE, "target skip fraction #%d = %g is outside [0, 1]", l, (double)target_skip_fractions[l]);
-    std::vector<float> host;
-    bsfa::FwdParams fp;
-    s = block_maxima_to_host(p, q, k, causal, workspace, workspace_bytes, hip_stream, host, fp);
+    if (!thresholds_out) return fail(BSFA_ERR_NULL, "thresholds_out must be non-NULL");
+    const size_t need = bsfa_calibrate_workspace_bytes(p);
+    if (!workspace || workspace_bytes < need)
+        return fail(BSFA_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    const size_t mq = (size_t)((p->seqlen + p->block_m - 1) / p->block_m), mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
+    const uintptr_t dump = up256(reinterpret_cast<uintptr_t>(workspace));
+    const uintptr_t area = up256(dump + (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float));
+    const uintptr_t outd = up256(area + bsfa::select_area_bytes(p->n_q_heads));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    s = calibrate_on_device(p, q, k, causal, target_skip_fractions, n_levels, reinterpret_cast<float *>(dump),
+                            reinterpret_cast<void *>(area), reinterpret_cast<float *>(outd), stream);
     if (s != BSFA_OK) return s;
-
-    // selection on the host: per head, order statistic of the gateable block maxima
-    const size_t per_head = (size_t)fp.mq * fp.mkv;
-    std::vector<float> vals;
-    for (int h = 0; h < p->n_q_heads; ++h) {
-        vals.clear();
-        for (int b = 0; b < p->batch; ++b) {
-            const float *src = host.data() + ((size_t)b * p->n_q_heads + h) * per_head;
-            for (size_t x = 0; x < per_head; ++x)
-                if (!std::isnan(src[x])) vals.push_back(src[x]);
-        }
-        const size_t n = vals.size();
-        for (int l = 0; l < n_levels; ++l) {
-            const size_t r = (size_t)std::floor((double)target_skip_fractions[l] * (double)n);
-            float t;
-            if (r == 0) t = -INFINITY;
-            else if (r >= n) t = INFINITY;
-            else {
-                std::nth_element(vals.begin(), vals.begin() + r, vals.end());
-                t = vals[r];
-            }
-            thresholds_out[(size_t)l * p->n_q_heads + h] = t;
-        }
-    }
+    // only n_levels x n_q_heads floats travel to the host
+    hipError_t e = hipMemcpyAsync(thresholds_out, reinterpret_cast<const void *>(outd), (size_t)n_levels * p->n_q_heads * sizeof(float),
+                                  hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration copy failed: %s", hipGetErrorString(e));
     return BSFA_OK;
 }
 

@@ -37,4 +37,19 @@ hipError_t launch_forward(const FwdParams &p, int head_dim, int block_m, bool ca
 
 bool shape_supported(int head_dim, int block_m, int block_n);
 
+// ---- order statistics of the block maxima on the GPU (bsfa_select.hip) ------------------------
+constexpr int kMaxLevels = 64;        // target skip fractions per calibration call
+constexpr int kLevelsPerRound = 8;    // levels that share one sweep over the block-maximum dump
+struct SelectLevels {
+    float f[kMaxLevels];              // target skip fractions, passed to the kernels by value
+};
+// Bytes of the histogram / state area launch_select needs for hq query heads (multiple of 16).
+size_t select_area_bytes(int hq);
+// dump: DEVICE [batch][hq][per_head] block maxima, NaN = not gateable.  out_dev: DEVICE
+// [n_levels][hq]: per head (batch elements pooled) the order statistic x_r, r = floor(f * n), of its
+// n non-NaN values, -inf if r == 0, +inf if r >= n.  area: DEVICE, select_area_bytes(hq) bytes,
+// 16-byte aligned; it is cleared by the launch.  Enqueues on stream; no host synchronisation.
+hipError_t launch_select(const float *dump, long per_head, int batch, int hq, const SelectLevels &lv, int n_levels,
+                         void *area, float *out_dev, hipStream_t stream);
+
 }  // namespace bsfa
