@@ -154,6 +154,25 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
                            void *hip_stream);
 
 /*
+ * bsfa_calibrate for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same thresholds as bsfa_calibrate, bit for bit,
+ * but the block maxima and the selection histograms live in a scratch array built into the library
+ * (about 21 MiB of device memory per GPU, held until the process ends), the results are written to
+ * DEVICE memory, and the call only enqueues kernels on hip_stream: no allocation, no memset, no copy,
+ * no host synchronisation.
+ *   thresholds_out_device DEVICE [n_levels][n_q_heads], usable as bsfa_forward thresholds once the
+ *                         stream has reached this point
+ * Limits (BSFA_ERR_WORKSPACE beyond them): batch * n_q_heads * M_Q * M_KV block maxima must not exceed
+ * bsfa_calibrate_noalloc_max_values() (4 Mi: e.g. 32 heads at 32K tokens with 128 x 64 tiles), and
+ * n_q_heads <= 64.  All calls on one GPU share the one scratch array: calls that overlap in time on
+ * the same GPU (different streams or threads) race and give undefined thresholds.
+ */
+bsfa_status bsfa_calibrate_noalloc(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                   const float *target_skip_fractions, int n_levels,
+                                   float *thresholds_out_device, void *hip_stream);
+size_t bsfa_calibrate_noalloc_max_values(void);
+
+/*
  * Calibration of per-query-tile thresholds, the rule of Section 4.2 itself: for every query head
  * and query tile, the threshold that retains exactly the top-k gateable key blocks of a
  * calibration sample (the k-th largest block maximum; -INFINITY where the tile has at most k

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libbsfa.so")
 BSFA_OK = 0
 STATUS_NAMES = {0: "BSFA_OK", -1: "BSFA_ERR_NULL", -2: "BSFA_ERR_SHAPE", -3: "BSFA_ERR_DTYPE",
                 -4: "BSFA_ERR_UNSUPPORTED", -5: "BSFA_ERR_WORKSPACE", -6: "BSFA_ERR_HIP"}
-EXPORTS = ["bsfa_forward", "bsfa_forward_workspace_bytes", "bsfa_calibrate", "bsfa_calibrate_topk",
+EXPORTS = ["bsfa_forward", "bsfa_forward_workspace_bytes", "bsfa_calibrate", "bsfa_calibrate_noalloc",
+           "bsfa_calibrate_noalloc_max_values", "bsfa_calibrate_topk",
            "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
            "bsfa_status_string", "bsfa_last_error"]
 
@@ -73,6 +74,11 @@ def lib() -> ctypes.CDLL:
         L.bsfa_calibrate.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
                                      ctypes.POINTER(ctypes.c_float), ctypes.c_int,
                                      ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
+        L.bsfa_calibrate_noalloc.restype = ctypes.c_int
+        L.bsfa_calibrate_noalloc.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
+                                             ctypes.POINTER(ctypes.c_float), ctypes.c_int, vp, vp]
+        L.bsfa_calibrate_noalloc_max_values.restype = ctypes.c_size_t
+        L.bsfa_calibrate_noalloc_max_values.argtypes = []
         L.bsfa_calibrate_topk.restype = ctypes.c_int
         L.bsfa_calibrate_topk.argtypes = [ctypes.POINTER(bsfa_problem), vp, vp, ctypes.c_int,
                                           ctypes.POINTER(ctypes.c_int32), ctypes.c_int, ctypes.c_int,
@@ -243,6 +249,25 @@ def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequ
                                 workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 ctypes.c_void_p(s.cuda_stream)))
     return torch.tensor(list(outp), dtype=torch.float32).view(n, q.shape[2])
+
+
+def bsfa_calibrate_noalloc(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequence[float],
+                           thresholds_out: torch.Tensor, causal: bool = True, block_m: int = 128, block_n: int = 64,
+                           stream: Optional[torch.cuda.Stream] = None,
+                           seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """bsfa_calibrate without allocations: the thresholds go to ``thresholds_out``, a contiguous
+    float32 GPU tensor [n_levels, Hq] the caller provides; kernels are only enqueued."""
+    _dev_check(q, k, thresholds_out)
+    _same_16bit("bsfa_calibrate_noalloc", q, k)
+    n = len(target_skip_fractions)
+    if thresholds_out.dtype != torch.float32 or not thresholds_out.is_contiguous() or tuple(thresholds_out.shape) != (n, q.shape[2]):
+        raise TypeError("bsfa_calibrate_noalloc: thresholds_out must be contiguous float32 [n_levels, Hq]")
+    p = make_problem(q, k, None, None, block_m, block_n, seqlens=seqlens)
+    fr = (ctypes.c_float * n)(*[float(f) for f in target_skip_fractions])
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    _check(lib().bsfa_calibrate_noalloc(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), fr, n,
+                                        thresholds_out.data_ptr(), ctypes.c_void_p(s.cuda_stream)))
+    return thresholds_out
 
 
 def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m: int = 128, block_n: int = 64,

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <functional>
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -222,6 +223,67 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(BSFA_ERR_HIP, "calibration copy failed: %s", hipGetErrorString(e));
     return BSFA_OK;
+}
+
+// ---- calibration without any allocation -----------------------------------------------------------
+// Scratch memory of bsfa_calibrate_noalloc: the block-maximum dump, the selection area and nothing
+// else, in a file-scope device array that every GPU the library runs on holds until the process
+// ends.  In host code the array's name is only a handle: its device address is looked up once per
+// device (with that device current) and the kernels get that address, never the name.
+constexpr size_t kScratchDumpBytes = (size_t)16 << 20;          // block maxima: 4 Mi values
+constexpr int kScratchMaxHeads = 64;                            // n_q_heads the selection area is sized for
+constexpr size_t kScratchAreaBytes = ((size_t)(1 + bsfa::kLevelsPerRound) * kScratchMaxHeads * 2048 * 4
+                                      + (size_t)bsfa::kLevelsPerRound * kScratchMaxHeads * 16 + 255) & ~(size_t)255;
+constexpr size_t kScratchBytes = kScratchDumpBytes + kScratchAreaBytes;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];                        // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+// Device address of this device's copy of the scratch array (looked up on first use), or null with
+// the error recorded.
+static unsigned char *scratch_address()
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(BSFA_ERR_HIP, "cannot identify the current device (%s)", e == hipSuccess ? "index out of range" : hipGetErrorString(e));
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(BSFA_ERR_HIP, "scratch array address lookup failed: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return static_cast<unsigned char *>(g_scratch_ptr[dev]);
+}
+
+size_t bsfa_calibrate_noalloc_max_values(void) { return kScratchDumpBytes / sizeof(float); }
+
+bsfa_status bsfa_calibrate_noalloc(const bsfa_problem *p, const void *q, const void *k, int causal,
+                                   const float *target_skip_fractions, int n_levels,
+                                   float *thresholds_out_device, void *hip_stream)
+{
+    bsfa_status s = check_problem(p, causal);
+    if (s != BSFA_OK) return s;
+    if (!thresholds_out_device) return fail(BSFA_ERR_NULL, "thresholds_out_device must be non-NULL");
+    const size_t mq = (size_t)((p->seqlen + p->block_m - 1) / p->block_m), mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
+    const size_t values = (size_t)p->batch * p->n_q_heads * mq * mkv;
+    if (values * sizeof(float) > kScratchDumpBytes)
+        return fail(BSFA_ERR_WORKSPACE, "batch * n_q_heads * M_Q * M_KV = %zu block maxima exceed the %zu the built-in scratch array holds "
+                                        "(use bsfa_calibrate with a workspace)", values, kScratchDumpBytes / sizeof(float));
+    if (p->n_q_heads > kScratchMaxHeads)
+        return fail(BSFA_ERR_WORKSPACE, "n_q_heads = %d exceeds the %d the built-in scratch array is sized for", p->n_q_heads, kScratchMaxHeads);
+    unsigned char *base = scratch_address();
+    if (!base) return BSFA_ERR_HIP;
+    return calibrate_on_device(p, q, k, causal, target_skip_fractions, n_levels, reinterpret_cast<float *>(base),
+                               base + kScratchDumpBytes, thresholds_out_device, static_cast<hipStream_t>(hip_stream));
 }
 
 bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,
