@@ -3,11 +3,15 @@
 
 A step is one bsfa_forward call (every stage of the hot path: Q load, K stream, QK^T, block
 maximum, gate, and for kept blocks V fetch, online softmax, PV, then finalisation and skip
-statistics) on the headline workload: one Llama-3.1-8B-shaped attention layer (B=1, 32 query
-heads, 8 KV heads, d=128, causal, bf16) at N=131072 with per-head thresholds calibrated on a
-separate seed for ~50 % block skip.  Inputs are synthetic and resident in HBM before timing.
-The same kernel with thresholds = -inf (its dense path) is timed next to it, and the CPU oracle
-is timed on a bounded sample of the same workload, which doubles as a parity check.
+statistics; the once-per-call rewrite of V into the forward workspace is part of the step) on
+the headline workload: one Llama-3.1-8B-shaped attention layer (B=1, 32 query heads, 8 KV heads,
+d=128, causal, bf16) at N=131072 with per-head thresholds calibrated on a separate seed for ~50 %
+block skip.  Inputs are synthetic and resident in HBM before timing.  The same kernel with
+thresholds = -inf (its dense path) is timed next to it.  The same line also carries the sparsity
+sweep at 128K (25 / 75 / 90 % skip) and the 32K and 64K sizes at 50 % skip, every point with its
+time, dense-equivalent TFLOP/s, executed fraction of the MFMA peak, skip efficiency and the error
+against the CPU oracle on sampled (head, query tile) items.  The CPU oracle is timed on a bounded
+sample of the headline workload.
 
 Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W [--seqlen N] [--skip F]`.
 """
@@ -33,10 +37,12 @@ def main():
     ap.add_argument("--seqlen", type=int, default=131072)
     ap.add_argument("--skip", type=float, default=0.5, help="target skip fraction of gateable tiles")
     ap.add_argument("--block-m", type=int, default=128)
-    ap.add_argument("--sweep", default="", help="comma-separated extra skip targets, e.g. 0.25,0.75,0.9: adds a "
-                                                "'sweep' list (time, measured skip, speed-up, eta per target) to the JSON line")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
-    ap.add_argument("--cpu-items", type=int, default=0, help="oracle sample size (0 = sized for ~20 s)")
+    ap.add_argument("--sweep", default="0.25,0.75,0.9",
+                    help="comma-separated extra skip targets at --seqlen ('' for none): adds a 'sweep' list")
+    ap.add_argument("--sizes", default="32768,65536",
+                    help="comma-separated extra sequence lengths timed at --skip and dense ('' for none): adds a 'sizes' list")
+    ap.add_argument("--no-cpu", action="store_true", help="skip every CPU-oracle leg (baseline and per-point parity)")
+    ap.add_argument("--no-workspace", action="store_true", help="run bsfa_forward without its workspace (V read in place)")
     ap.add_argument("--traffic-json", default=None, help="file with measured HBM bytes per launch (from rocprofv3 --pmc)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain elementwise copy of Q into O (known size: reads and writes "
@@ -56,117 +62,59 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    shp = synth.llama_shape(args.seqlen, block_m=args.block_m)
-    bm, bn, d = shp.block_m, shp.block_n, shp.head_dim
-
-    # calibration sample (seed 1) -> thresholds; evaluation sample (seed 0)
-    qc, kc, _ = synth.llama_layer(1, shp, device=dev)
-    ws = torch.empty(binding.lib().bsfa_calibrate_workspace_bytes(binding.make_problem(qc, kc, None, None, bm, bn)),
-                     dtype=torch.uint8, device=dev)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    bn = 64
+    bm = args.block_m
     sweep_targets = [float(x) for x in args.sweep.split(",") if x]
-    taus = binding.bsfa_calibrate(qc, kc, [args.skip] + sweep_targets, block_m=bm, block_n=bn, workspace=ws)
-    tau = taus[0]
-    t_calib = time.perf_counter() - t0
-    del qc, kc, ws
-    torch.cuda.empty_cache()
-    q, k, v = synth.llama_layer(0, shp, device=dev)
-    out = torch.empty_like(q)
-    tau_d = tau.to(dev)
-    neg_d = torch.full_like(tau_d, float("-inf"))
-    st = binding.alloc_stats(q, bm, bn, counts=True)
-
-    def timed(thr, steps, warmup):
-        for _ in range(warmup):
-            binding.bsfa_forward(q, k, v, thr, out=out, skip_stats=st, block_m=bm, block_n=bn)
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        t_wall = time.perf_counter()
-        ev[0].record()
-        for s in range(steps):
-            binding.bsfa_forward(q, k, v, thr, out=out, skip_stats=st, block_m=bm, block_n=bn)
-            ev[s + 1].record()
-        torch.cuda.synchronize()
-        t_wall = time.perf_counter() - t_wall
-        per = [ev[s].elapsed_time(ev[s + 1]) for s in range(steps)]       # ms, includes the tiny counter-reset launch
-        return t_wall * 1e3 / steps, per, st.counts.cpu().numpy().copy()
-
-    if args.copy_probe:
-        torch.add(q, 0, out=out)
-        torch.cuda.synchronize()
-    ms_sparse, per_sparse, c_sparse = timed(tau_d, args.steps, args.warmup)
-    ms_dense, per_dense, c_dense = timed(neg_d, args.steps, args.warmup)
-
-    tile_flops = 2.0 * bm * bn * d                         # one of the two contractions on one tile
-    f_dense_equiv = 4.0 * d * shp.n_q_heads * shp.batch * float(shp.seqlen) ** 2 / 2.0
-    reach = float(c_sparse[..., 2].sum())
-    skipped = float(c_sparse[..., 0].sum())
-    gateable = float(c_sparse[..., 1].sum())
-    f_exec_sparse = tile_flops * (2 * reach - skipped)
-    f_exec_dense = tile_flops * 2 * reach
-    kern_ms_sparse = float(np.mean(per_sparse))
-    kern_ms_dense = float(np.mean(per_dense))
-    tf_sparse_equiv = f_dense_equiv / (ms_sparse * 1e-3) / 1e12
-    tf_dense = f_dense_equiv / (ms_dense * 1e-3) / 1e12
-    exec_tf_sparse = f_exec_sparse / (kern_ms_sparse * 1e-3) / 1e12
-    exec_tf_dense = f_exec_dense / (kern_ms_dense * 1e-3) / 1e12
-    f_skip = skipped / reach
-    speedup = ms_dense / ms_sparse
-    eta = (1.0 - ms_sparse / ms_dense) / (f_skip / 2.0) if f_skip > 0 else None
-
-    # HBM bytes per launch of the gated kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-    # scaled by a known-size copy; read from the file written from those runs
-    traffic = None
-    tj = args.traffic_json or os.path.join(ROOT, "profiles", "bsfa_fwd_kernel_traffic.json")
-    if os.path.exists(tj):
-        rec = json.load(open(tj))
-        if rec.get("seqlen") == shp.seqlen:
-            traffic = rec.get("hbm_bytes_per_launch_gated")
-
-    result = {
-        "metric": "dense-equiv attention TFLOP/s at ~50% block skip (speedup vs own dense path beside it)",
-        "value": round(tf_sparse_equiv, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_sparse, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "Llama-3.1-8B attention layer prefill, B=1 Hq=32 Hkv=8 d=128 causal N=%d, tile %dx%d, "
-                               "per-head tau calibrated on a separate seed for %.0f%% skip" % (shp.seqlen, bm, bn, 100 * args.skip),
-                   "seqlen": shp.seqlen, "target_skip": args.skip},
-        "skip_fraction_of_reachable": round(f_skip, 4), "skip_fraction_of_gateable": round(skipped / gateable, 4),
-        "dense_path": {"ms_per_step": round(ms_dense, 3), "tflops": round(tf_dense, 2),
-                       "mfma_frac_executed": round(exec_tf_dense / PEAK_BF16_TFLOPS, 4)},
-        "speedup_vs_own_dense": round(speedup, 4), "ideal_speedup": round(2 / (2 - f_skip), 4),
-        "skip_efficiency_eta": None if eta is None else round(eta, 4),
-        "step_ms_min_median": [round(float(np.min(per_sparse)), 3), round(float(np.median(per_sparse)), 3)],
-        "calibrate_s": round(t_calib, 3),
-        "roofline": {"bound": "mfma", "kernel": "bsfa_fwd_kernel (gated, %.0f%% skip)" % (100 * f_skip),
-                     "achieved": round(exec_tf_sparse, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(exec_tf_sparse / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                     "flops_per_launch": f_exec_sparse, "kernel_ms": round(kern_ms_sparse, 3)},
-    }
-
-    if sweep_targets:
-        sweep = []
-        for f_t, t_l in zip(sweep_targets, taus[1:]):
-            ms_l, _, c_l = timed(t_l.to(dev), max(3, args.steps // 2), 1)
-            f_l = float(c_l[..., 0].sum()) / float(c_l[..., 2].sum())
-            sweep.append({"target_skip": f_t, "skip_fraction_of_reachable": round(f_l, 4), "ms_per_step": round(ms_l, 3),
-                          "dense_equiv_tflops": round(f_dense_equiv / (ms_l * 1e-3) / 1e12, 2),
-                          "speedup_vs_own_dense": round(ms_dense / ms_l, 4), "ideal_speedup": round(2 / (2 - f_l), 4),
-                          "skip_efficiency_eta": round((1.0 - ms_l / ms_dense) / (f_l / 2.0), 4) if f_l > 0 else None})
-        result["sweep"] = sweep
-
+    sizes = [int(x) for x in args.sizes.split(",") if x and int(x) != args.seqlen]
     if not args.no_cpu:
         from oracle import bsfa_oracle as orc
         from tests import parity
         orc.build()
-        # bounded sample of (head, query tile) items of the same workload, ~20 s of oracle time
-        items = parity.sample_items(shp, n_random=8, seed=0)
-        if args.cpu_items:
-            items = items[:args.cpu_items]
-        else:
-            # oracle cost grows with the tile index; cap the summed reachable key blocks
-            budget = 1.2e6
+
+    def measure(seqlen, targets, steps, warmup, parity_budget):
+        """Dense path and every skip target at one sequence length.  Returns (shape, tensors, thresholds,
+        list of point records); the first record is the dense path."""
+        shp = synth.llama_shape(seqlen, block_m=bm)
+        d = shp.head_dim
+        qc, kc, _ = synth.llama_layer(1, shp, device=dev)               # calibration sample (seed 1)
+        ws = torch.empty(binding.lib().bsfa_calibrate_workspace_bytes(binding.make_problem(qc, kc, None, None, bm, bn)),
+                         dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        taus = binding.bsfa_calibrate(qc, kc, targets, block_m=bm, block_n=bn, workspace=ws)
+        t_calib = time.perf_counter() - t0
+        del qc, kc, ws
+        torch.cuda.empty_cache()
+        q, k, v = synth.llama_layer(0, shp, device=dev)                 # evaluation sample (seed 0)
+        out = torch.empty_like(q)
+        fws = None
+        if not args.no_workspace:
+            fws = torch.empty(binding.forward_workspace_bytes(q, k, bm, bn), dtype=torch.uint8, device=dev)
+        st = binding.alloc_stats(q, bm, bn, counts=True)
+        tile_flops = 2.0 * bm * bn * d                                  # one of the two contractions on one tile
+        f_dense_equiv = 4.0 * d * shp.n_q_heads * shp.batch * float(seqlen) ** 2 / 2.0
+
+        def fwd(thr, stats):
+            binding.bsfa_forward(q, k, v, thr, out=out, skip_stats=stats, block_m=bm, block_n=bn, workspace=fws)
+
+        def timed(thr):
+            for _ in range(warmup):
+                fwd(thr, st)
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            t_wall = time.perf_counter()
+            ev[0].record()
+            for s in range(steps):
+                fwd(thr, st)
+                ev[s + 1].record()
+            torch.cuda.synchronize()
+            t_wall = time.perf_counter() - t_wall
+            per = [ev[s].elapsed_time(ev[s + 1]) for s in range(steps)]   # ms on the launch stream (incl. the small side kernels)
+            return t_wall * 1e3 / steps, per, st.counts.cpu().numpy().copy()
+
+        def check(thr_host, thr_dev, budget, n_random):
+            """Sampled oracle parity of the launch just timed (block budget bounds the CPU time)."""
+            items = parity.sample_items(shp, n_random=n_random, seed=seqlen % 997)
             keep, tot = [], 0
             for it in sorted(items, key=lambda x: x[2]):
                 nb = -(-((it[2] + 1) * bm) // bn)
@@ -174,23 +122,116 @@ def main():
                     continue
                 keep.append(it)
                 tot += nb
-            items = keep
-        bst = binding.alloc_stats(q, bm, bn, counts=False, skip_mask=True)
-        binding.bsfa_forward(q, k, v, tau_d, out=out, skip_stats=bst, block_m=bm, block_n=bn)
+            bst = binding.alloc_stats(q, bm, bn, counts=False, skip_mask=True)
+            fwd(thr_dev, bst)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            r = orc.forward_items(qh, kh, vh, thr_host.numpy(), bm, bn, True, keep)
+            t_cpu = time.perf_counter() - t0
+            rep = parity.compare(qh, kh, vh, thr_host, bm, bn, True, out, bst.skip_mask, None, items=keep, oracle_result=r)
+            return rep, r, t_cpu, keep
+
+        if not args.no_cpu:
+            qh, kh, vh = q.float().cpu(), k.float().cpu(), v.float().cpu()
+        points = []
+        neg = torch.full((shp.n_q_heads,), float("-inf"))
+        ms_dense = None
+        for target, thr in [(0.0, neg)] + list(zip(targets, taus)):
+            thr_d = thr.to(dev)
+            ms, per, c = timed(thr_d)
+            reach, skipped, gateable = float(c[..., 2].sum()), float(c[..., 0].sum()), float(c[..., 1].sum())
+            f_exec = tile_flops * (2 * reach - skipped)
+            kern_ms = float(np.mean(per))
+            f_skip = skipped / reach
+            if ms_dense is None:
+                ms_dense = ms
+            rec = {"seqlen": seqlen, "target_skip": target, "skip_fraction_of_reachable": round(f_skip, 4),
+                   "skip_fraction_of_gateable": round(skipped / gateable, 4) if gateable else 0.0,
+                   "ms_per_step": round(ms, 3), "kernel_ms": round(kern_ms, 3),
+                   "step_ms_min_median": [round(float(np.min(per)), 3), round(float(np.median(per)), 3)],
+                   "dense_equiv_tflops": round(f_dense_equiv / (ms * 1e-3) / 1e12, 2),
+                   "executed_tflops": round(f_exec / (kern_ms * 1e-3) / 1e12, 2),
+                   "mfma_frac_executed": round(f_exec / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                   "flops_per_launch": f_exec,
+                   "speedup_vs_own_dense": round(ms_dense / ms, 4), "ideal_speedup": round(2 / (2 - f_skip), 4),
+                   "skip_efficiency_eta": round((1.0 - ms / ms_dense) / (f_skip / 2.0), 4) if f_skip > 0 else None}
+            if not args.no_cpu:
+                rep, _, t_cpu, _ = check(thr, thr_d, parity_budget, 1)
+                rec["parity"] = {"items": rep.n_items, "max_abs": rep.max_abs, "mean_abs": rep.mean_abs,
+                                 "mask_mismatch_in_band": rep.mask_mismatch, "tiles_in_band": rep.in_band,
+                                 "oracle_s": round(t_cpu, 2)}
+            points.append(rec)
+        ctx = dict(shp=shp, q=q, k=k, v=v, out=out, taus=taus, t_calib=t_calib, check=check if not args.no_cpu else None,
+                   tile_flops=tile_flops, reach=float(points[0]["flops_per_launch"] / (2 * tile_flops)))
+        return ctx, points
+
+    # ---- headline size: dense, --skip, sweep -----------------------------------------------------
+    ctx, pts = measure(args.seqlen, [args.skip] + sweep_targets, args.steps, args.warmup, 1.5e5)
+    if args.copy_probe:
+        torch.add(ctx["q"], 0, out=ctx["out"])
         torch.cuda.synchronize()
-        qh, kh, vh = q.float().cpu(), k.float().cpu(), v.float().cpu()
-        t0 = time.perf_counter()
-        r = orc.forward_items(qh, kh, vh, tau.numpy(), bm, bn, True, items)
-        t_cpu = time.perf_counter() - t0
+    dense, head = pts[0], pts[1]
+    shp = ctx["shp"]
+
+    # HBM bytes per launch of the gated kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+    # scaled by a known-size copy; not measured in this run but read from the file written from those runs
+    traffic, traffic_source = None, None
+    tj = args.traffic_json or os.path.join(ROOT, "profiles", "bsfa_fwd_kernel_traffic.json")
+    if os.path.exists(tj):
+        rec = json.load(open(tj))
+        if rec.get("seqlen") == shp.seqlen:
+            traffic = rec.get("hbm_bytes_per_launch_gated")
+            traffic_source = os.path.relpath(tj, ROOT) + " (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier run, scaled by a known-size copy)"
+
+    result = {
+        "metric": "dense-equiv attention TFLOP/s at ~50% block skip (speedup vs own dense path beside it)",
+        "value": head["dense_equiv_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "Llama-3.1-8B attention layer prefill, B=1 Hq=32 Hkv=8 d=128 causal N=%d, tile %dx%d, "
+                               "per-head tau calibrated on a separate seed for %.0f%% skip" % (shp.seqlen, bm, bn, 100 * args.skip),
+                   "seqlen": shp.seqlen, "target_skip": args.skip, "forward_workspace": not args.no_workspace},
+        "skip_fraction_of_reachable": head["skip_fraction_of_reachable"], "skip_fraction_of_gateable": head["skip_fraction_of_gateable"],
+        "dense_path": {"ms_per_step": dense["ms_per_step"], "tflops": dense["dense_equiv_tflops"],
+                       "mfma_frac_executed": dense["mfma_frac_executed"]},
+        "speedup_vs_own_dense": head["speedup_vs_own_dense"], "ideal_speedup": head["ideal_speedup"],
+        "skip_efficiency_eta": head["skip_efficiency_eta"],
+        "step_ms_min_median": head["step_ms_min_median"],
+        "calibrate_s": round(ctx["t_calib"], 3),
+        "roofline": {"bound": "mfma", "kernel": "bsfa_fwd_kernel (gated, %.0f%% skip)" % (100 * head["skip_fraction_of_reachable"]),
+                     "achieved": head["executed_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": head["mfma_frac_executed"], "traffic": traffic, "traffic_source": traffic_source,
+                     "flops_per_launch": head["flops_per_launch"], "kernel_ms": head["kernel_ms"]},
+    }
+    if "parity" in dense:
+        result["dense_path"]["parity"] = dense["parity"]
+    if sweep_targets:
+        result["sweep"] = pts[2:]
+
+    if not args.no_cpu:
+        # CPU baseline: the oracle on a bounded sample of (head, query tile) items of the headline launch
+        # (~15 s of oracle time), which is also one more parity check
+        n_random = 8
+        rep, r, t_cpu, items = ctx["check"](ctx["taus"][0], ctx["taus"][0].to(dev), 9e5, n_random)
         units = int((r.cls != orc.CLS_UNREACHABLE).sum())
-        cpu_tf = 2 * tile_flops * units / t_cpu / 1e12
-        rep = parity.compare(q, k, v, tau, bm, bn, True, out, bst.skip_mask, None, items=items, oracle_result=r)
+        cpu_tf = 2 * ctx["tile_flops"] * units / t_cpu / 1e12
         result["cpu_baseline"] = {"value": round(cpu_tf, 6), "unit": "TFLOP/s (dense-equivalent)", "cores": orc.threads(),
                                   "kind": "oracle", "seconds": round(t_cpu, 2),
                                   "sample": "%d (head, query-tile) items = %d tile x key-block units of the same inputs; "
-                                            "full problem extrapolates to %.0f s" % (len(items), units, t_cpu / units * reach)}
+                                            "full problem extrapolates to %.0f s" % (len(items), units, t_cpu / units * ctx["reach"])}
         result["parity"] = {"items": rep.n_items, "max_abs": rep.max_abs, "mean_abs": rep.mean_abs,
                             "mask_mismatch_in_band": rep.mask_mismatch, "tiles_in_band": rep.in_band}
+    del ctx
+    torch.cuda.empty_cache()
+
+    # ---- the other sequence lengths: dense and --skip ------------------------------------------------
+    if sizes:
+        result["sizes"] = []
+        for n in sizes:
+            c2, p2 = measure(n, [args.skip], max(args.steps, 10), args.warmup, 1.0e5)
+            result["sizes"].append({"seqlen": n, "dense": p2[0], "gated": p2[1], "calibrate_s": round(c2["t_calib"], 3)})
+            del c2
+            torch.cuda.empty_cache()
     print(json.dumps(result))
 
 
