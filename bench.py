@@ -41,6 +41,8 @@ def main():
                     help="comma-separated extra skip targets at --seqlen ('' for none): adds a 'sweep' list")
     ap.add_argument("--sizes", default="32768,65536",
                     help="comma-separated extra sequence lengths timed at --skip and dense ('' for none): adds a 'sizes' list")
+    ap.add_argument("--noncausal", type=int, default=32768,
+                    help="sequence length of the bidirectional leg (causal = 0; dense and --skip); 0 for none")
     ap.add_argument("--no-cpu", action="store_true", help="skip every CPU-oracle leg (baseline and per-point parity)")
     ap.add_argument("--no-workspace", action="store_true", help="run bsfa_forward without its workspace (V read in place)")
     ap.add_argument("--traffic-json", default=None, help="file with measured HBM bytes per launch (from rocprofv3 --pmc)")
@@ -71,7 +73,7 @@ def main():
         from tests import parity
         orc.build()
 
-    def measure(seqlen, targets, steps, warmup, parity_budget):
+    def measure(seqlen, targets, steps, warmup, parity_budget, causal=True):
         """Dense path and every skip target at one sequence length.  Returns (shape, tensors, thresholds,
         list of point records); the first record is the dense path."""
         shp = synth.llama_shape(seqlen, block_m=bm)
@@ -81,7 +83,7 @@ def main():
                          dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        taus = binding.bsfa_calibrate(qc, kc, targets, block_m=bm, block_n=bn, workspace=ws)
+        taus = binding.bsfa_calibrate(qc, kc, targets, causal=causal, block_m=bm, block_n=bn, workspace=ws)
         t_calib = time.perf_counter() - t0
         del qc, kc, ws
         torch.cuda.empty_cache()
@@ -92,10 +94,10 @@ def main():
             fws = torch.empty(binding.forward_workspace_bytes(q, k, bm, bn), dtype=torch.uint8, device=dev)
         st = binding.alloc_stats(q, bm, bn, counts=True)
         tile_flops = 2.0 * bm * bn * d                                  # one of the two contractions on one tile
-        f_dense_equiv = 4.0 * d * shp.n_q_heads * shp.batch * float(seqlen) ** 2 / 2.0
+        f_dense_equiv = 4.0 * d * shp.n_q_heads * shp.batch * float(seqlen) ** 2 / (2.0 if causal else 1.0)
 
         def fwd(thr, stats):
-            binding.bsfa_forward(q, k, v, thr, out=out, skip_stats=stats, block_m=bm, block_n=bn, workspace=fws)
+            binding.bsfa_forward(q, k, v, thr, causal=causal, out=out, skip_stats=stats, block_m=bm, block_n=bn, workspace=fws)
 
         def timed(thr):
             for _ in range(warmup):
@@ -117,7 +119,7 @@ def main():
             items = parity.sample_items(shp, n_random=n_random, seed=seqlen % 997)
             keep, tot = [], 0
             for it in sorted(items, key=lambda x: x[2]):
-                nb = -(-((it[2] + 1) * bm) // bn)
+                nb = -(-((it[2] + 1) * bm) // bn) if causal else shp.m_kv
                 if tot + nb > budget and keep:
                     continue
                 keep.append(it)
@@ -126,9 +128,9 @@ def main():
             fwd(thr_dev, bst)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            r = orc.forward_items(qh, kh, vh, thr_host.numpy(), bm, bn, True, keep)
+            r = orc.forward_items(qh, kh, vh, thr_host.numpy(), bm, bn, causal, keep)
             t_cpu = time.perf_counter() - t0
-            rep = parity.compare(qh, kh, vh, thr_host, bm, bn, True, out, bst.skip_mask, None, items=keep, oracle_result=r)
+            rep = parity.compare(qh, kh, vh, thr_host, bm, bn, causal, out, bst.skip_mask, None, items=keep, oracle_result=r)
             return rep, r, t_cpu, keep
 
         if not args.no_cpu:
@@ -145,7 +147,7 @@ def main():
             f_skip = skipped / reach
             if ms_dense is None:
                 ms_dense = ms
-            rec = {"seqlen": seqlen, "target_skip": target, "skip_fraction_of_reachable": round(f_skip, 4),
+            rec = {"seqlen": seqlen, "causal": causal, "target_skip": target, "skip_fraction_of_reachable": round(f_skip, 4),
                    "skip_fraction_of_gateable": round(skipped / gateable, 4) if gateable else 0.0,
                    "ms_per_step": round(ms, 3), "kernel_ms": round(kern_ms, 3),
                    "step_ms_min_median": [round(float(np.min(per)), 3), round(float(np.median(per)), 3)],
@@ -232,6 +234,12 @@ def main():
             result["sizes"].append({"seqlen": n, "dense": p2[0], "gated": p2[1], "calibrate_s": round(c2["t_calib"], 3)})
             del c2
             torch.cuda.empty_cache()
+    # ---- bidirectional attention (causal = 0): dense and --skip ------------------------------------
+    if args.noncausal:
+        c3, p3 = measure(args.noncausal, [args.skip], max(args.steps, 10), args.warmup, 1.0e5, causal=False)
+        result["noncausal"] = {"seqlen": args.noncausal, "dense": p3[0], "gated": p3[1]}
+        del c3
+        torch.cuda.empty_cache()
     print(json.dumps(result))
 
 

@@ -460,17 +460,24 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     wait_vmcnt<0>();                                       // drained once; from here on the steady-state rule holds
     wg_barrier();
 
-    // main loop: pairs of stages whose look-ahead block is gateable (causal only), then the rest
+    // main loop, two stages per trip.  A pair runs the fused, mask-free stages when both of its
+    // look-ahead blocks (j+1, j+2) exist and are gateable: every pair below the causal boundary;
+    // without the causal mask every pair before the tile's own token range and, in a second
+    // segment, every pair behind it (Section 4.3, last sentence: only the own-range blocks bypass the
+    // gate).  The remaining pairs take the general stages.
     int j = 0;
-    if (p.causal) {
-        for (; j + 2 < n_gate; j += 2) {
+    for (int seg = 0; seg < 2; ++seg) {
+        const int fast_end = seg == 0 ? (p.causal ? n_gate : own_lo) : (p.causal ? 0 : n_blk);
+        for (; j + 2 < fast_end; j += 2) {
             stage(ta, tb, j, std::true_type{});
             stage(tb, ta, j + 1, std::true_type{});
         }
-    }
-    for (; j < n_blk; j += 2) {
-        stage(ta, tb, j, std::false_type{});
-        if (j + 1 < n_blk) stage(tb, ta, j + 1, std::false_type{});
+        // first even j whose look-ahead block lies behind the own range
+        const int gen_end = (seg == 0 && !p.causal) ? min(own_hi & ~1, n_blk) : n_blk;
+        for (; j < gen_end; j += 2) {
+            stage(ta, tb, j, std::false_type{});
+            if (j + 1 < n_blk) stage(tb, ta, j + 1, std::false_type{});
+        }
     }
 
     // ---- statistics ------------------------------------------------------------------------
