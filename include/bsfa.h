@@ -89,6 +89,17 @@ typedef struct {
                                      skip).  1: one query head per workgroup — the heads' skip decisions
                                      no longer share a barrier, which is faster when most blocks are
                                      skipped.  Results are identical either way. */
+    int32_t gate_mode;            /* optional, bsfa_forward only.  0: the paper's gate (block maximum against the
+                                     threshold, Section 4.1).  1: the running-maximum predicate the paper
+                                     describes for SpargeAttention's in-kernel filter (Section 3), provided for
+                                     comparison inside the same kernel: with m_local the row maxima of the score
+                                     tile and m_ij the running row maxima after the block (kept blocks only,
+                                     ascending block order), a gateable block is skipped iff
+                                     max over the tile's rows of (m_local - m_ij) < thresholds[h]; the
+                                     thresholds then hold that lambda (natural score units, <= 0 to skip
+                                     anything) instead of T, block_max holds the compared statistic, and the
+                                     blocks that bypass the gate are the same.  Decisions now depend on the
+                                     visiting order (ascending), unlike mode 0. */
     void   *workspace;            /* optional, DEVICE, 256-byte aligned, bsfa_forward only: scratch memory of at
                                      least bsfa_forward_workspace_bytes() bytes, overwritten by every call.
                                      With it (and block_m = 128) the forward pass first rewrites V, once, as

@@ -13,6 +13,9 @@ Two independent forms of the same result live here:
   visits the gateable blocks in any order the caller gives, which is what pins the claim that
   the two forms agree.
 
+``alg1_tile_running_max`` is the same loop with the comparison predicate of Section 3 (local
+row maxima against the running maxima) in place of the paper's gate.
+
 ``calibrate`` is the per-head threshold rule: an order statistic of the block maxima of the
 gateable tiles (Section 4.2 sorts blocks by their maximum and picks the threshold retaining a
 target count; the per-head quantile is the reduction of that rule over query positions).
@@ -260,6 +263,54 @@ def alg1_tile(q, k, v, tau_h, b, h, i, block_m, block_n, order=None):
         update(S, v[b, j * block_n:(j + 1) * block_n, g, :])
         kept.append(j)
     return O / l[:, None], m + np.log(l), kept
+
+
+def alg1_tile_running_max(q, k, v, lam_h, b, h, i, block_m, block_n):
+    """The comparison predicate of Section 3 (the in-kernel filter the paper describes for
+    SpargeAttention) inside the loop of Algorithm 1, for one query block i of head h (causal,
+    ascending block order, which the decisions now depend on).
+
+    For a gateable block with score tile S_ij: m_local = row maxima of S_ij, m_ij = the running
+    row maxima after the block, max(m_{i,j-1}, m_local), where m_{i,j-1} runs over the kept
+    blocks before j (-inf before the first).  The block is skipped iff
+    max over rows (m_local - m_ij) < lambda; skipped blocks leave (m, l, O) untouched.  The blocks
+    that touch the causal boundary are processed ungated, as in Algorithm 1.
+    Returns (O_i [B_M, d], L_i [B_M], kept block indices, statistic per gateable block as fp32)."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, N, Hq, d = q.shape
+    g = h // (Hq // k.shape[2])
+    Qi = q[b, i * block_m:(i + 1) * block_m, h, :]
+    m = np.full(block_m, -np.inf)
+    l = np.zeros(block_m)
+    O = np.zeros((block_m, d))
+    n_reach = -(-((i + 1) * block_m) // block_n)
+    kept, stats = [], {}
+    for j in range(n_reach):
+        Kj = k[b, j * block_n:(j + 1) * block_n, g, :]
+        Vj = v[b, j * block_n:(j + 1) * block_n, g, :]
+        S = Qi @ Kj.T / np.sqrt(d)
+        gateable = (j + 1) * block_n - 1 <= i * block_m
+        if gateable:
+            m_local = S.max(axis=1)
+            m_ij = np.maximum(m, m_local)
+            stat = np.float32((m_local - m_ij).max())
+            stats[j] = stat
+            if stat < np.float32(lam_h):
+                continue
+        else:
+            rows = i * block_m + np.arange(block_m)[:, None]
+            cols = j * block_n + np.arange(block_n)[None, :]
+            S = np.where(cols > rows, -np.inf, S)
+        m_new = np.maximum(m, S.max(axis=1))
+        P = np.exp(S - m_new[:, None])
+        alpha = np.exp(m - m_new)
+        O = O * alpha[:, None] + P @ Vj
+        l = l * alpha + P.sum(axis=1)
+        m = m_new
+        kept.append(j)
+    return O / l[:, None], m + np.log(l), kept, stats
 
 
 # --------------------------------------------------------------------------------------

@@ -45,7 +45,7 @@ class bsfa_problem(ctypes.Structure):
                  "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
                [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32),
                 ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p),
-                ("single_head_groups", ctypes.c_int32), ("workspace", ctypes.c_void_p),
+                ("single_head_groups", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("workspace", ctypes.c_void_p),
                 ("workspace_bytes", ctypes.c_int64)]
 
 
@@ -188,12 +188,13 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
                  stream: Optional[torch.cuda.Stream] = None,
                  seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False,
-                 workspace=True) -> torch.Tensor:
+                 workspace=True, gate_mode: int = 0) -> torch.Tensor:
     """out = block-sparse attention of bf16 (or fp16) q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
     GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
     GPU tensor [B], causal only) gives each batch element its own length.  ``workspace``: a uint8
     GPU tensor of at least forward_workspace_bytes(...) bytes, True (a cached tensor per device is
-    used) or False/None (no workspace: V is read in place).  Enqueues on ``stream`` (default:
+    used) or False/None (no workspace: V is read in place).  ``gate_mode`` 1 selects the
+    running-maximum comparison predicate (thresholds then hold its lambda).  Enqueues on ``stream`` (default:
     torch's current stream)."""
     _dev_check(q, k, v, thresholds, out)
     _same_16bit("bsfa_forward", q, k, v, *([out] if out is not None else []))
@@ -207,6 +208,7 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
         out = torch.empty_like(q)
     p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens,
                      single_head_groups)
+    p.gate_mode = int(gate_mode)
     if workspace is True:
         workspace = _cached_workspace(q.device, lib().bsfa_forward_workspace_bytes(ctypes.byref(p)))
     if workspace is not None and workspace is not False:

@@ -55,6 +55,7 @@ bsfa_status check_problem(const bsfa_problem *p, int causal)
     if (p->threshold_tiles < 0) return fail(BSFA_ERR_SHAPE, "threshold_tiles must not be negative");
     if (p->single_head_groups != 0 && p->single_head_groups != 1) return fail(BSFA_ERR_SHAPE, "single_head_groups must be 0 or 1");
     if (p->workspace_bytes < 0) return fail(BSFA_ERR_WORKSPACE, "workspace_bytes must not be negative");
+    if (p->gate_mode != 0 && p->gate_mode != 1) return fail(BSFA_ERR_SHAPE, "gate_mode must be 0 or 1");
     return BSFA_OK;
 }
 
@@ -76,6 +77,7 @@ void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
     fp.causal = causal ? 1 : 0;
     fp.f16 = (p->dtype == BSFA_FP16) ? 1 : 0;
     fp.single_head = p->single_head_groups ? 1 : 0;
+    fp.gate_mode = p->gate_mode;
     fp.tau_per_tile = p->thresholds_per_tile;
     fp.scale = 1.0f / sqrtf((float)p->head_dim);
     fp.scale_log2 = (float)(1.4426950408889634 / sqrt((double)p->head_dim));
@@ -171,6 +173,7 @@ static bsfa_status calibrate_on_device(const bsfa_problem *p, const void *q, con
                                        float *dump, void *area, float *out_dev, hipStream_t stream)
 {
     if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "per-head calibration produces per-head thresholds only");
+    if (p->gate_mode) return fail(BSFA_ERR_UNSUPPORTED, "calibration is defined for the block-maximum gate (gate_mode 0) only");
     if (!q || !k || !target_skip_fractions) return fail(BSFA_ERR_NULL, "q, k and fractions must be non-NULL");
     if (!aligned16(q) || !aligned16(k)) return fail(BSFA_ERR_SHAPE, "q and k must be 16-byte aligned");
     if (n_levels < 1 || n_levels > bsfa::kMaxLevels) return fail(BSFA_ERR_SHAPE, "n_levels must be between 1 and %d", bsfa::kMaxLevels);
@@ -293,6 +296,7 @@ bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void
     bsfa_status s = check_problem(p, causal);
     if (s != BSFA_OK) return s;
     if (p->seqlens) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate_topk takes samples of one length (seqlens must be NULL)");
+    if (p->gate_mode) return fail(BSFA_ERR_UNSUPPORTED, "calibration is defined for the block-maximum gate (gate_mode 0) only");
     if (!q || !k || !ks || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, ks and thresholds_out must be non-NULL");
     if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
     if (samples_done < 0) return fail(BSFA_ERR_SHAPE, "samples_done must be non-negative");

@@ -224,7 +224,13 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t.s[kb][e]);
         t.mx = pair_max(mx);
         if (gated) {
-            const float wm = wave_max_paired(t.mx);
+            float stat = t.mx;
+            if constexpr (!FAST) {
+                // the comparison predicate (Section 3): local row maximum minus the running row maximum
+                // after this block, natural units; m_run covers the kept blocks before this one
+                if (p.gate_mode) stat = fminf(t.mx * p.scale - m_run * 0.6931471805599453f, 0.f);
+            }
+            const float wm = wave_max_paired(stat);
             if (lane == 0) lds_red[j & 1][wave] = wm;
         }
     };
@@ -243,7 +249,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                 float r = red[x * NWH];
 #pragma unroll
                 for (int w = 1; w < NWH; ++w) r = fmaxf(r, red[x * NWH + w]);
-                const float sm = r * p.scale;                        // natural score units (Eq. 5-6)
+                const float sm = (!FAST && p.gate_mode) ? r : r * p.scale;   // natural score units (Eq. 5-6)
                 const bool kx = (sm >= tau_h[x]);                    // skip iff s_max < T
                 any_keep = any_keep || kx;
                 if (x == hsel) {
@@ -467,7 +473,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // gate).  The remaining pairs take the general stages.
     int j = 0;
     for (int seg = 0; seg < 2; ++seg) {
-        const int fast_end = seg == 0 ? (p.causal ? n_gate : own_lo) : (p.causal ? 0 : n_blk);
+        const int fast_end = p.gate_mode ? 0 : seg == 0 ? (p.causal ? n_gate : own_lo) : (p.causal ? 0 : n_blk);
         for (; j + 2 < fast_end; j += 2) {
             stage(ta, tb, j, std::true_type{});
             stage(tb, ta, j + 1, std::true_type{});

@@ -20,6 +20,7 @@ struct FwdParams {
     int causal, tau_per_tile, tau_tiles;
     int f16;                         // element type of q, k, v, out: 0 bf16, 1 fp16
     int single_head;                 // 1: never pair the heads of a GQA group in one workgroup
+    int gate_mode;                   // 0: block maximum vs threshold; 1: running-maximum predicate (general stages only)
     float scale;                     // 1/sqrt(d): natural score units, used by the gate
     float scale_log2;                // log2(e)/sqrt(d): softmax evaluated with exp2
     unsigned long long *counts;      // [batch][hq][3] or null

@@ -314,3 +314,70 @@ def test_workspace_path_is_bit_identical_to_in_place_v(case, dtype):
     with pytest.raises(binding.BsfaError) as e:
         binding.bsfa_forward(q, k, v, tau, workspace=ws[:need - 1024])
     assert e.value.status == -5
+
+
+def test_running_max_predicate_matches_algorithm(oracle):
+    """gate_mode = 1, the comparison predicate of Section 3, against its step-by-step oracle form:
+    statistic per (tile, block) to 1e-4, decisions exactly (lambda is placed where no statistic of
+    the oracle's own trajectory lies within 1e-3 of it, so no decision can legitimately flip and
+    drag the running maximum with it), outputs within the usual tolerance of the exact softmax
+    over the kept blocks."""
+    shp = synth.Shape(1, 1024, 4, 2, 128, 128, 64)
+    g = torch.Generator().manual_seed(5)
+    u = torch.nn.functional.normalize(torch.randn(128, generator=g), dim=0)
+    q = 3.0 * u + 0.5 * torch.randn(1, 1024, 4, 128, generator=g)
+    k = torch.randn(1, 1024, 2, 128, generator=g)
+    # block 0 sets a high running maximum; blocks 3 and 9 come within |lambda| of it, 6 and 12 do not
+    for blk, amp in ((0, 40.0), (3, 36.0), (9, 36.0), (6, 30.0), (12, 30.0)):
+        k[:, blk * 64:(blk + 1) * 64] += amp * u
+    v = torch.randn(1, 1024, 2, 128, generator=g)
+    qd, kd, vd = to_dev(q, k, v)
+    qf, kf, vf = (t.float().cpu().numpy() for t in (qd, kd, vd))
+    lam0 = -2.0
+    # oracle trajectories; move lambda away from any statistic that is too close
+    def run_oracle(lam):
+        res = {}
+        for h in range(4):
+            for i in range(shp.m_q):
+                res[(h, i)] = oracle.alg1_tile_running_max(qf, kf, vf, lam, 0, h, i, 128, 64)
+        return res
+    lam = lam0
+    for _ in range(20):
+        res = run_oracle(lam)
+        near = [abs(float(s) - lam) for r in res.values() for s in r[3].values()]
+        if min(near) > 2e-3:
+            break
+        lam -= 0.0137
+    else:
+        pytest.fail("no clear lambda found")
+    lam_d = torch.full((4,), lam, device=DEV)
+    st = binding.alloc_stats(qd, 128, 64, counts=True, skip_mask=True, block_max=True, lse=True)
+    out = binding.bsfa_forward(qd, kd, vd, lam_d, skip_stats=st, gate_mode=1)
+    torch.cuda.synchronize()
+    mask = parity.unpack_mask(st.skip_mask.cpu().numpy(), shp.m_kv)[0]        # [h, i, j] True = skipped
+    bmx = st.block_max.cpu().numpy()[0]
+    o = out.float().cpu().numpy()[0]
+    lse = st.lse.cpu().numpy()[0]
+    n_skipped = 0
+    for (h, i), (O, L, kept, stats) in res.items():
+        n_reach = 2 * i + 2
+        skipped = [j for j in range(n_reach) if j not in kept]
+        assert list(np.nonzero(mask[h, i])[0]) == skipped, (h, i)
+        n_skipped += len(skipped)
+        for j, s_ in stats.items():
+            assert abs(bmx[h, i, j] - float(s_)) < 1e-4
+        assert np.isnan(bmx[h, i, len(stats):]).all()
+        err = np.abs(o[i * 128:(i + 1) * 128, h] - O)
+        assert err.max() <= parity.MAX_ABS and err.mean() <= parity.MEAN_ABS
+        assert np.abs(lse[i * 128:(i + 1) * 128, h] - L).max() < 5e-3
+    assert n_skipped > 20
+    assert int(st.counts[0, :, 0].sum()) == n_skipped
+    # the same call with gate_mode 0 takes the thresholds as T: a different mask
+    st0 = binding.alloc_stats(qd, 128, 64, counts=True)
+    binding.bsfa_forward(qd, kd, vd, lam_d, skip_stats=st0)
+    torch.cuda.synchronize()
+    assert int(st0.counts[0, :, 0].sum()) == 0            # every block maximum is far above -2
+    kept_gate = sum(len([j for j in r[2] if j in r[3] and j > 0]) for r in res.values())
+    assert kept_gate > 5                                  # and some gateable blocks behind the first survive
+    with pytest.raises(binding.BsfaError):
+        binding.bsfa_forward(qd, kd, vd, lam_d, gate_mode=2)

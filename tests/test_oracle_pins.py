@@ -31,8 +31,9 @@ def brute_attention(q, k, v, causal=True, key_keep=None):
     S = brute_scores(q, k, causal)
     if key_keep is not None:
         S = np.where(key_keep, S, -np.inf)
-    P = np.exp(S - S.max(axis=-1, keepdims=True))
-    P /= P.sum(axis=-1, keepdims=True)
+    with np.errstate(invalid="ignore"):          # rows left without any key (partial key_keep masks) become NaN
+        P = np.exp(S - S.max(axis=-1, keepdims=True))
+        P /= P.sum(axis=-1, keepdims=True)
     G = q.shape[2] // v.shape[2]
     vv = np.repeat(np.asarray(v, np.float64), G, axis=2)
     return np.einsum("bhnm,bmhd->bnhd", P, vv), P
@@ -483,3 +484,92 @@ def test_p14_topk_thresholds_are_the_mean_over_samples(oracle):
     one = oracle.calibrate_topk(samples[:1], gate, ks)
     f1 = np.isfinite(per_sample[0])
     np.testing.assert_array_equal(one[f1], per_sample[0][f1].astype(np.float32))
+
+
+# ---- the comparison predicate of Section 3 (running-maximum filter) ---------------------------------
+def test_p15_running_max_predicate_limits_and_error_bound(oracle):
+    """lambda = -inf keeps everything (dense); lambda = +inf keeps nothing the gate applies to (the
+    statistic is never above 0); for lambda <= 0 every skipped score lies at least |lambda| below its
+    row's final maximum, so the dense softmax mass of the skipped keys is at most
+    n_skipped_keys * exp(lambda) and the output moves by at most twice that times max|V|."""
+    shp, q, k, v = make(CASES[1], seed=61)
+    bm, bn = shp.block_m, shp.block_n
+    dense, _ = brute_attention(q, k, v)
+    _, P = brute_attention(q, k, v)
+    N = shp.seqlen
+    for b in range(shp.batch):
+        for h in range(shp.n_q_heads):
+            for i in range(shp.m_q):
+                sl = slice(i * bm, (i + 1) * bm)
+                gate = [j for j in range(shp.m_kv) if (j + 1) * bn - 1 <= i * bm]
+                reach = [j for j in range(shp.m_kv) if j * bn <= (i + 1) * bm - 1]
+                O, L, kept, st = oracle.alg1_tile_running_max(q, k, v, -np.inf, b, h, i, bm, bn)
+                assert kept == reach and np.abs(O - dense[b, sl, h]).max() < 2e-6
+                assert all(x <= 0 for x in st.values())
+                O, L, kept, st = oracle.alg1_tile_running_max(q, k, v, np.inf, b, h, i, bm, bn)
+                assert kept == [j for j in reach if j not in gate]
+                own = np.zeros((1, 1, N, N), bool)
+                for j in kept:
+                    own[0, 0, sl, j * bn:(j + 1) * bn] = True
+                ref, _ = brute_attention(q[b:b + 1, :, h:h + 1], k[b:b + 1, :, h // shp.group:h // shp.group + 1],
+                                         v[b:b + 1, :, h // shp.group:h // shp.group + 1], key_keep=own)
+                assert np.abs(O - ref[0, sl, 0]).max() < 2e-6
+    # a problem on which the predicate does skip: queries share a direction and the first key block is
+    # boosted along it, so the running maximum is set early and most later blocks fall far below it
+    big = synth.Shape(1, 1024, 2, 1, 16, 128, 64)
+    rng = np.random.default_rng(7)
+    u = rng.normal(size=16); u /= np.linalg.norm(u)
+    q = (3.0 * u + 0.4 * rng.normal(size=(1, 1024, 2, 16))).astype(np.float32)
+    k = rng.normal(size=(1, 1024, 1, 16)).astype(np.float32)
+    k[:, :64] += (4.0 * u).astype(np.float32)
+    v = rng.normal(size=(1, 1024, 1, 16)).astype(np.float32)
+    dense, P = brute_attention(q, k, v)
+    N, skipped_any, kept_any = 1024, 0, 0
+    for lam in (-0.5, -2.0, -6.0):
+        for h in range(2):
+            for i in (3, 7):
+                sl = slice(i * bm, (i + 1) * bm)
+                O, L, kept, st = oracle.alg1_tile_running_max(q, k, v, lam, 0, h, i, bm, bn)
+                skipped = [j for j in st if j not in kept]
+                skipped_any += len(skipped)
+                kept_any += len([j for j in st if j in kept and j > 0])
+                delta = np.zeros(bm)
+                for j in skipped:
+                    delta += P[0, h, sl, j * bn:(j + 1) * bn].sum(-1)
+                assert (delta <= len(skipped) * bn * np.exp(lam) + 1e-12).all()
+                assert (np.abs(O - dense[0, sl, h]).max(-1) <= 2 * delta * np.abs(v).max() + 1e-6).all()
+                # the kept set reproduces the output: exact softmax over the kept blocks
+                keep = np.zeros((1, 1, N, N), bool)
+                for j in kept:
+                    keep[0, 0, sl, j * bn:(j + 1) * bn] = True
+                ref, _ = brute_attention(q[:1, :, h:h + 1], k, v, key_keep=keep)
+                assert np.abs(O - ref[0, sl, 0]).max() < 2e-6
+    assert skipped_any > 10 and kept_any > 0
+
+
+def test_p16_running_max_predicate_closed_form(oracle):
+    """All queries equal e, all keys of block j equal a_j e: every score of block j is a_j |e|^2 / sqrt(d).
+    Decreasing a_j: the running maximum stays at block 0's value and block j is kept iff
+    (a_j - a_0) |e|^2 / sqrt(d) >= lambda.  Increasing a_j: every block raises the maximum, the statistic
+    is 0 and everything is kept for any lambda <= 0."""
+    d, bm, bn, N = 16, 128, 64, 1024
+    e = np.ones(d) / 2.0
+    c = (e @ e) / np.sqrt(d)                                  # score per unit of a_j
+    q = np.broadcast_to(e, (1, N, 1, d)).astype(np.float32).copy()
+    rng = np.random.default_rng(3)
+    v = rng.normal(size=(1, N, 1, d)).astype(np.float32)
+    i = N // bm - 1
+    gate = [j for j in range(N // bn) if (j + 1) * bn - 1 <= i * bm]
+    a_dec = np.linspace(4.0, -4.0, N // bn)
+    k = (np.repeat(a_dec, bn)[None, :, None, None] * e[None, None, None, :]).astype(np.float32)
+    lam = -3.0
+    O, L, kept, st = oracle.alg1_tile_running_max(q, k, v, lam, 0, 0, i, bm, bn)
+    expect = [j for j in gate if np.float32((a_dec[j] - a_dec[0]) * c) >= np.float32(lam)]
+    assert 1 < len(expect) < len(gate)
+    assert [j for j in kept if j in gate] == expect
+    for j in gate[1:]:
+        assert abs(st[j] - (a_dec[j] - a_dec[0]) * c) < 1e-5
+    a_inc = a_dec[::-1].copy()
+    k = (np.repeat(a_inc, bn)[None, :, None, None] * e[None, None, None, :]).astype(np.float32)
+    O, L, kept, st = oracle.alg1_tile_running_max(q, k, v, lam, 0, 0, i, bm, bn)
+    assert [j for j in kept if j in gate] == gate and all(x == 0 for x in st.values())
