@@ -43,6 +43,8 @@ def main():
                     help="comma-separated extra sequence lengths timed at --skip and dense ('' for none): adds a 'sizes' list")
     ap.add_argument("--noncausal", type=int, default=32768,
                     help="sequence length of the bidirectional leg (causal = 0; dense and --skip); 0 for none")
+    ap.add_argument("--no-fp8-leg", action="store_true",
+                    help="skip the leg that runs the score product on fp8 copies of Q and K (dense and --skip at --seqlen)")
     ap.add_argument("--no-cpu", action="store_true", help="skip every CPU-oracle leg (baseline and per-point parity)")
     ap.add_argument("--no-workspace", action="store_true", help="run bsfa_forward without its workspace (V read in place)")
     ap.add_argument("--traffic-json", default=None, help="file with measured HBM bytes per launch (from rocprofv3 --pmc)")
@@ -73,17 +75,16 @@ def main():
         from tests import parity
         orc.build()
 
-    def measure(seqlen, targets, steps, warmup, parity_budget, causal=True):
+    def measure(seqlen, targets, steps, warmup, parity_budget, causal=True, qk_fp8=False):
         """Dense path and every skip target at one sequence length.  Returns (shape, tensors, thresholds,
         list of point records); the first record is the dense path."""
         shp = synth.llama_shape(seqlen, block_m=bm)
         d = shp.head_dim
         qc, kc, _ = synth.llama_layer(1, shp, device=dev)               # calibration sample (seed 1)
-        ws = torch.empty(binding.lib().bsfa_calibrate_workspace_bytes(binding.make_problem(qc, kc, None, None, bm, bn)),
-                         dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        taus = binding.bsfa_calibrate(qc, kc, targets, causal=causal, block_m=bm, block_n=bn, workspace=ws)
+        taus = binding.bsfa_calibrate(qc, kc, targets, causal=causal, block_m=bm, block_n=bn, qk_fp8=qk_fp8)
+        ws = None
         t_calib = time.perf_counter() - t0
         del qc, kc, ws
         torch.cuda.empty_cache()
@@ -91,13 +92,14 @@ def main():
         out = torch.empty_like(q)
         fws = None
         if not args.no_workspace:
-            fws = torch.empty(binding.forward_workspace_bytes(q, k, bm, bn), dtype=torch.uint8, device=dev)
+            fws = torch.empty(binding.forward_workspace_bytes(q, k, bm, bn, qk_fp8=qk_fp8), dtype=torch.uint8, device=dev)
         st = binding.alloc_stats(q, bm, bn, counts=True)
         tile_flops = 2.0 * bm * bn * d                                  # one of the two contractions on one tile
         f_dense_equiv = 4.0 * d * shp.n_q_heads * shp.batch * float(seqlen) ** 2 / (2.0 if causal else 1.0)
 
         def fwd(thr, stats):
-            binding.bsfa_forward(q, k, v, thr, causal=causal, out=out, skip_stats=stats, block_m=bm, block_n=bn, workspace=fws)
+            binding.bsfa_forward(q, k, v, thr, causal=causal, out=out, skip_stats=stats, block_m=bm, block_n=bn, workspace=fws,
+                                 qk_fp8=qk_fp8)
 
         def timed(thr):
             for _ in range(warmup):
@@ -134,7 +136,11 @@ def main():
             return rep, r, t_cpu, keep
 
         if not args.no_cpu:
-            qh, kh, vh = q.float().cpu(), k.float().cpu(), v.float().cpu()
+            if qk_fp8:      # the oracle gets what the score product multiplies: Q and K rounded to fp8 (e4m3, nearest even)
+                qh, kh = (t.to(torch.float8_e4m3fn).float().cpu() for t in (q, k))
+                vh = v.float().cpu()
+            else:
+                qh, kh, vh = q.float().cpu(), k.float().cpu(), v.float().cpu()
         points = []
         neg = torch.full((shp.n_q_heads,), float("-inf"))
         ms_dense = None
@@ -147,7 +153,7 @@ def main():
             f_skip = skipped / reach
             if ms_dense is None:
                 ms_dense = ms
-            rec = {"seqlen": seqlen, "causal": causal, "target_skip": target, "skip_fraction_of_reachable": round(f_skip, 4),
+            rec = {"seqlen": seqlen, "causal": causal, "qk_fp8": qk_fp8, "target_skip": target, "skip_fraction_of_reachable": round(f_skip, 4),
                    "skip_fraction_of_gateable": round(skipped / gateable, 4) if gateable else 0.0,
                    "ms_per_step": round(ms, 3), "kernel_ms": round(kern_ms, 3),
                    "step_ms_min_median": [round(float(np.min(per)), 3), round(float(np.median(per)), 3)],
@@ -234,6 +240,14 @@ def main():
             result["sizes"].append({"seqlen": n, "dense": p2[0], "gated": p2[1], "calibrate_s": round(c2["t_calib"], 3)})
             del c2
             torch.cuda.empty_cache()
+    # ---- score product on fp8 operands (qk_fp8 = 1): dense and --skip at the headline length ------------
+    if not args.no_fp8_leg and bm == 128:
+        c4, p4 = measure(args.seqlen, [args.skip], args.steps, args.warmup, 1.0e5, qk_fp8=True)
+        result["qk_fp8"] = {"seqlen": args.seqlen, "dense": p4[0], "gated": p4[1],
+                            "note": "Q and K rounded to fp8 e4m3 for the score product only; thresholds calibrated in the same mode; "
+                                    "parity is against the oracle on the rounded Q and K"}
+        del c4
+        torch.cuda.empty_cache()
     # ---- bidirectional attention (causal = 0): dense and --skip ------------------------------------
     if args.noncausal:
         c3, p3 = measure(args.noncausal, [args.skip], max(args.steps, 10), args.warmup, 1.0e5, causal=False)

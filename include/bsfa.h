@@ -100,6 +100,15 @@ typedef struct {
                                      anything) instead of T, block_max holds the compared statistic, and the
                                      blocks that bypass the gate are the same.  Decisions now depend on the
                                      visiting order (ascending), unlike mode 0. */
+    int32_t qk_fp8;               /* optional, 0 by default.  1: the score product Q K^T runs on fp8 (e4m3) copies of Q
+                                     and K (rounded to nearest even, no scaling: |values| must stay below 448) with
+                                     the 32x32x64 fp8 MFMA, fp32 accumulate; block maxima, the gate comparison, the
+                                     softmax and the P V product are unchanged (fp32 / 16-bit).  The paper calls
+                                     quantisation orthogonal to its gate (Section 5.1, Baselines); this is that
+                                     combination.  Needs head_dim 128, block_m 128 and the workspace (bsfa_forward)
+                                     resp. the larger calibration workspace; thresholds should be calibrated with
+                                     the same setting, since block maxima of fp8-rounded operands differ from the
+                                     16-bit ones by a few hundredths. */
     void   *workspace;            /* optional, DEVICE, 256-byte aligned, bsfa_forward only: scratch memory of at
                                      least bsfa_forward_workspace_bytes() bytes, overwritten by every call.
                                      With it (and block_m = 128) the forward pass first rewrites V, once, as
@@ -142,7 +151,8 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
                          const bsfa_skip_stats *skip_stats /* may be NULL */, void *hip_stream);
 
 /* Bytes of workspace bsfa_forward can use for *p (size of V rounded up to whole 64-key blocks, plus
- * alignment slack); 0 if *p is invalid or its tile shape makes no use of a workspace. */
+ * half as much for the fp8 copy of K if p->qk_fp8, plus alignment slack); 0 if *p is invalid or its
+ * tile shape makes no use of a workspace. */
 size_t bsfa_forward_workspace_bytes(const bsfa_problem *p);
 
 /*

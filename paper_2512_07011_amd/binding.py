@@ -45,7 +45,7 @@ class bsfa_problem(ctypes.Structure):
                  "v_stride_b", "v_stride_n", "v_stride_h", "o_stride_b", "o_stride_n", "o_stride_h")] + \
                [("dtype", ctypes.c_int32), ("thresholds_per_tile", ctypes.c_int32),
                 ("threshold_tiles", ctypes.c_int32), ("seqlens", ctypes.c_void_p),
-                ("single_head_groups", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("workspace", ctypes.c_void_p),
+                ("single_head_groups", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("qk_fp8", ctypes.c_int32), ("workspace", ctypes.c_void_p),
                 ("workspace_bytes", ctypes.c_int64)]
 
 
@@ -172,9 +172,12 @@ def _cached_workspace(device, nbytes: int):
     return w
 
 
-def forward_workspace_bytes(q: torch.Tensor, k: torch.Tensor, block_m: int = 128, block_n: int = 64) -> int:
+def forward_workspace_bytes(q: torch.Tensor, k: torch.Tensor, block_m: int = 128, block_n: int = 64,
+                            qk_fp8: bool = False) -> int:
     """Bytes of workspace bsfa_forward can use for these shapes (0: none)."""
-    return int(lib().bsfa_forward_workspace_bytes(ctypes.byref(make_problem(q, k, None, None, block_m, block_n))))
+    p = make_problem(q, k, None, None, block_m, block_n)
+    p.qk_fp8 = int(bool(qk_fp8))
+    return int(lib().bsfa_forward_workspace_bytes(ctypes.byref(p)))
 
 
 def _dev_check(*ts):
@@ -188,7 +191,7 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
                  skip_stats: Optional[SkipStats] = None, block_m: int = 128, block_n: int = 64,
                  stream: Optional[torch.cuda.Stream] = None,
                  seqlens: Optional[torch.Tensor] = None, single_head_groups: bool = False,
-                 workspace=True, gate_mode: int = 0) -> torch.Tensor:
+                 workspace=True, gate_mode: int = 0, qk_fp8: bool = False) -> torch.Tensor:
     """out = block-sparse attention of bf16 (or fp16) q [B,N,Hq,d], k, v [B,N,Hkv,d]; thresholds fp32 on the
     GPU, [Hq] or [Hq, T] (T tiles calibrated; later tiles use the last one).  ``seqlens`` (int32
     GPU tensor [B], causal only) gives each batch element its own length.  ``workspace``: a uint8
@@ -209,6 +212,7 @@ def bsfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, thresholds: 
     p = make_problem(q, k, v, out, block_m, block_n, per_tile, thresholds.shape[1] if per_tile else 0, seqlens,
                      single_head_groups)
     p.gate_mode = int(gate_mode)
+    p.qk_fp8 = int(bool(qk_fp8))
     if workspace is True:
         workspace = _cached_workspace(q.device, lib().bsfa_forward_workspace_bytes(ctypes.byref(p)))
     if workspace is not None and workspace is not False:
@@ -233,11 +237,12 @@ def bsfa_calibrate(q: torch.Tensor, k: torch.Tensor, target_skip_fractions: Sequ
                    causal: bool = True, block_m: int = 128, block_n: int = 64,
                    workspace: Optional[torch.Tensor] = None,
                    stream: Optional[torch.cuda.Stream] = None,
-                   seqlens: Optional[torch.Tensor] = None) -> torch.Tensor:
+                   seqlens: Optional[torch.Tensor] = None, qk_fp8: bool = False) -> torch.Tensor:
     """Per-head thresholds for each target skip fraction: CPU float32 tensor [n_levels, Hq]."""
     _dev_check(q, k, workspace)
     _same_16bit("bsfa_calibrate", q, k)
     p = make_problem(q, k, None, None, block_m, block_n, seqlens=seqlens)
+    p.qk_fp8 = int(bool(qk_fp8))
     need = lib().bsfa_calibrate_workspace_bytes(ctypes.byref(p))
     if need == 0:
         _check(lib().bsfa_calibrate(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), None, 0, None, None, 0, None))

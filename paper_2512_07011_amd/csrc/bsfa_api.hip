@@ -56,7 +56,17 @@ bsfa_status check_problem(const bsfa_problem *p, int causal)
     if (p->single_head_groups != 0 && p->single_head_groups != 1) return fail(BSFA_ERR_SHAPE, "single_head_groups must be 0 or 1");
     if (p->workspace_bytes < 0) return fail(BSFA_ERR_WORKSPACE, "workspace_bytes must not be negative");
     if (p->gate_mode != 0 && p->gate_mode != 1) return fail(BSFA_ERR_SHAPE, "gate_mode must be 0 or 1");
+    if (p->qk_fp8 != 0 && p->qk_fp8 != 1) return fail(BSFA_ERR_SHAPE, "qk_fp8 must be 0 or 1");
+    if (p->qk_fp8 && (p->head_dim != 128 || p->block_m != 128))
+        return fail(BSFA_ERR_UNSUPPORTED, "qk_fp8 needs head_dim 128 and block_m 128");
     return BSFA_OK;
+}
+
+// bytes of the fp8 copy of K: [batch][n_kv_heads][M_KV] tiles of block_n x head_dim bytes
+size_t k8_bytes(const bsfa_problem *p)
+{
+    const size_t mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
+    return (size_t)p->batch * p->n_kv_heads * mkv * (size_t)p->block_n * p->head_dim;
 }
 
 void fill_params(bsfa::FwdParams &fp, const bsfa_problem *p, int causal)
@@ -109,8 +119,10 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
             if ((size_t)p->workspace_bytes < need)
                 return fail(BSFA_ERR_WORKSPACE, "forward workspace of %zu bytes needed, %lld given", need, (long long)p->workspace_bytes);
             fp.vt = reinterpret_cast<uint16_t *>((reinterpret_cast<uintptr_t>(p->workspace) + 255) & ~(uintptr_t)255);
+            if (p->qk_fp8) fp.k8 = reinterpret_cast<uint8_t *>((reinterpret_cast<uintptr_t>(fp.vt) + 2 * k8_bytes(p) + 255) & ~(uintptr_t)255);
         }
     }
+    if (p->qk_fp8 && !fp.k8) return fail(BSFA_ERR_WORKSPACE, "qk_fp8 needs the forward workspace (bsfa_forward_workspace_bytes)");
     if (skip_stats) {
         fp.counts = reinterpret_cast<unsigned long long *>(skip_stats->counts);
         fp.skip_mask = skip_stats->skip_mask;
@@ -125,8 +137,8 @@ bsfa_status bsfa_forward(const bsfa_problem *p, const void *q, const void *k, co
 size_t bsfa_forward_workspace_bytes(const bsfa_problem *p)
 {
     if (check_problem(p, 1) != BSFA_OK || p->block_m != 128) return 0;
-    const size_t mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
-    return (size_t)p->batch * p->n_kv_heads * mkv * (size_t)p->block_n * p->head_dim * 2 + 256;
+    // transposed V tiles | fp8 K tiles (if asked for), each 256-byte aligned
+    return 2 * k8_bytes(p) + 256 + (p->qk_fp8 ? k8_bytes(p) + 256 : 0);
 }
 
 size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
@@ -135,7 +147,8 @@ size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p)
     const size_t mq = (size_t)((p->seqlen + p->block_m - 1) / p->block_m), mkv = (size_t)((p->seqlen + p->block_n - 1) / p->block_n);
     const size_t dump = (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float);
     // block-maximum dump | selection area | per-level results, each 256-byte aligned
-    return dump + bsfa::select_area_bytes(p->n_q_heads) + (size_t)bsfa::kMaxLevels * p->n_q_heads * sizeof(float) + 4 * 256;
+    return dump + bsfa::select_area_bytes(p->n_q_heads) + (size_t)bsfa::kMaxLevels * p->n_q_heads * sizeof(float) + 4 * 256
+           + (p->qk_fp8 ? k8_bytes(p) + 256 : 0);           // ... | fp8 K tiles
 }
 
 // Shared front half of the calibration entry points: checks, score / block-maximum kernel,
@@ -170,7 +183,7 @@ static bsfa_status block_maxima_to_host(const bsfa_problem *p, const void *q, co
 // stream; nothing is allocated and the host does not wait.
 static bsfa_status calibrate_on_device(const bsfa_problem *p, const void *q, const void *k, int causal,
                                        const float *target_skip_fractions, int n_levels,
-                                       float *dump, void *area, float *out_dev, hipStream_t stream)
+                                       float *dump, void *area, float *out_dev, uint8_t *k8, hipStream_t stream)
 {
     if (p->thresholds_per_tile) return fail(BSFA_ERR_UNSUPPORTED, "per-head calibration produces per-head thresholds only");
     if (p->gate_mode) return fail(BSFA_ERR_UNSUPPORTED, "calibration is defined for the block-maximum gate (gate_mode 0) only");
@@ -190,6 +203,7 @@ static bsfa_status calibrate_on_device(const bsfa_problem *p, const void *q, con
     fp.q = static_cast<const uint16_t *>(q);
     fp.k = static_cast<const uint16_t *>(k);
     fp.block_max = dump;
+    fp.k8 = k8;
     fp.tau = nullptr;                 // the score half takes no decisions and reads no thresholds
     fp.tau_per_tile = 0;
     fp.tau_tiles = 1;
@@ -217,8 +231,10 @@ bsfa_status bsfa_calibrate(const bsfa_problem *p, const void *q, const void *k, 
     const uintptr_t area = up256(dump + (size_t)p->batch * p->n_q_heads * mq * mkv * sizeof(float));
     const uintptr_t outd = up256(area + bsfa::select_area_bytes(p->n_q_heads));
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uintptr_t k8 = up256(outd + (size_t)bsfa::kMaxLevels * p->n_q_heads * sizeof(float));
     s = calibrate_on_device(p, q, k, causal, target_skip_fractions, n_levels, reinterpret_cast<float *>(dump),
-                            reinterpret_cast<void *>(area), reinterpret_cast<float *>(outd), stream);
+                            reinterpret_cast<void *>(area), reinterpret_cast<float *>(outd),
+                            p->qk_fp8 ? reinterpret_cast<uint8_t *>(k8) : nullptr, stream);
     if (s != BSFA_OK) return s;
     // only n_levels x n_q_heads floats travel to the host
     hipError_t e = hipMemcpyAsync(thresholds_out, reinterpret_cast<const void *>(outd), (size_t)n_levels * p->n_q_heads * sizeof(float),
@@ -285,8 +301,9 @@ bsfa_status bsfa_calibrate_noalloc(const bsfa_problem *p, const void *q, const v
         return fail(BSFA_ERR_WORKSPACE, "n_q_heads = %d exceeds the %d the built-in scratch array is sized for", p->n_q_heads, kScratchMaxHeads);
     unsigned char *base = scratch_address();
     if (!base) return BSFA_ERR_HIP;
+    if (p->qk_fp8) return fail(BSFA_ERR_UNSUPPORTED, "qk_fp8 is not available without a workspace (use bsfa_calibrate)");
     return calibrate_on_device(p, q, k, causal, target_skip_fractions, n_levels, reinterpret_cast<float *>(base),
-                               base + kScratchDumpBytes, thresholds_out_device, static_cast<hipStream_t>(hip_stream));
+                               base + kScratchDumpBytes, thresholds_out_device, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,

@@ -44,6 +44,22 @@ __device__ __forceinline__ float pair_sum(f16x2_t pp, float acc)
     const f16x2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
     return __builtin_amdgcn_fdot2(pp, ones, acc, false);
 }
+// 32x32x64 MFMA on fp8 (e4m3) operands, fp32 accumulate: a lane holds 32 consecutive bytes of the
+// contraction dimension of its row (A) or column (B); block scales fixed at 2^0
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x16 mfma64_fp8(i32x8 a, i32x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
+}
+// eight fp32 -> two dwords of fp8 (e4m3), round to nearest even
+__device__ __forceinline__ void cvt8_fp8(const float (&f)[8], int &w0, int &w1)
+{
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+    w0 = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], w0, true);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+    w1 = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], w1, true);
+}
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -78,20 +94,20 @@ __device__ __forceinline__ uint32_t chunk_src_offset(int r, int tid, int stride_
     return (uint32_t)(min(row, rows - 1) * stride_n + 8 * c) * 2u;
 }
 
-// Asynchronous HBM -> LDS copy of one 64 x D tile; lds_tile is the byte address of the tile's
-// slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  The tile's first
+// Asynchronous HBM -> LDS copy of one tile in NREP repetitions of NT x 16 bytes (NREP = 64 * D * 2 /
+// 16 / NT for a 64 x D tile of 16-bit elements); lds_tile is the byte address of the tile's slot.  Each lane fetches 16 bytes; the hardware writes them at M0 + lane * 16.  The tile's first
 // row is addressed through a scalar base (it is the same for the whole workgroup), each lane adds
 // its 32-bit byte offset (callers pass a base computed from workgroup-uniform values only; a base
 // the compiler cannot prove uniform is rejected at build time, the asm operand being a scalar pair).
 // Completion is tracked by vmcnt, which this kernel manages itself
 // (wait_vmcnt): the instruction is emitted through inline asm so that the compiler does not
 // serialise every later LDS read behind all copies in flight.
-template <int D, int NT>
-__device__ __forceinline__ void tile_copy_async(const uint16_t *gtile, const uint32_t (&off)[64 * (D / 8) / NT],
+template <int NREP, int NT>
+__device__ __forceinline__ void tile_copy_async(const void *gtile, const uint32_t (&off)[NREP],
                                                 uint32_t lds_tile, int wave)
 {
 #pragma unroll
-    for (int r = 0; r < 64 * (D / 8) / NT; ++r) {
+    for (int r = 0; r < NREP; ++r) {
         const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(r * NT + wave * 64) * 16u);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
@@ -114,7 +130,7 @@ __device__ __forceinline__ void tile_copy_async_clamped(const uint16_t *gtile, i
     uint32_t off[64 * (D / 8) / NT];
 #pragma unroll
     for (int r = 0; r < 64 * (D / 8) / NT; ++r) off[r] = chunk_src_offset<D, NT, ISV>(r, tid, stride_n, rows);
-    tile_copy_async<D, NT>(gtile, off, lds_tile, wave);
+    tile_copy_async<64 * (D / 8) / NT, NT>(gtile, off, lds_tile, wave);
 }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, no wait on the others)

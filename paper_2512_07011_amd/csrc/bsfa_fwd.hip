@@ -36,7 +36,7 @@ struct ScoreTile {
     float alpha;          // kept blocks: factor that rescales the running accumulator and normaliser
 };
 
-template <int D, int NWH, int HP, int KR, bool CALIB, bool F16, bool VT>
+template <int D, int NWH, int HP, int KR, bool CALIB, bool F16, bool VT, bool QK8>
 __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdParams p)
 {
     typedef typename Elem<F16>::T el;                    // element type of Q, K, V, P, O
@@ -50,12 +50,14 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     constexpr int KS = D / 16;       // MFMA k-steps over the head dim
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int CPR = D / 8;       // 16-byte chunks per tile row
-    constexpr int NST = 64 * CPR / NT;
+    constexpr int NST = 64 * CPR / NT;                   // copy repetitions per 16-bit tile (V; K unless QK8)
+    constexpr int NSTK = QK8 ? NST / 2 : NST;            // ... per K tile (fp8 tiles are half the bytes)
+    static_assert(!QK8 || (D == 128 && NST >= 2), "fp8 score operands: head_dim 128, at most 512 threads");
     constexpr int TILE_BYTES = BN * D * 2;
     constexpr int ROW_BYTES = D * 2;
     constexpr int R = KR + 1;        // K tiles are requested R blocks ahead
     constexpr int VR = CALIB ? 0 : 2;
-    static_assert(NST >= 1 && (R < 4 || NST * (R - 3) < 64), "copy repetitions");
+    static_assert(NST >= 1 && (R < 4 || NSTK * (R - 3) < 64), "copy repetitions");
 
     __shared__ __attribute__((aligned(1024))) unsigned char lds_raw[(KR + VR) * TILE_BYTES];
     __shared__ float lds_red[2][NW];
@@ -108,28 +110,38 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         tau_h[x] = CALIB ? -INFINITY      // the score half takes no decisions
                          : p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
 
-    uint32_t koff[NST], voff[NST];
+    uint32_t koff[NSTK], voff[NST];
 #pragma unroll
     for (int r = 0; r < NST; ++r) {
-        koff[r] = chunk_src_offset<D, NT, false>(r, tid, (int)p.ksn);
+        if (r < NSTK) koff[r] = QK8 ? (uint32_t)(r * NT + tid) * 16u : chunk_src_offset<D, NT, false>(r, tid, (int)p.ksn);
         voff[r] = VT ? (uint32_t)(r * NT + tid) * 16u : chunk_src_offset<D, NT, true>(r, tid, (int)p.vsn);
     }
+    // QK8: K comes from the workspace as fp8 tiles (64 rows of D bytes, swizzled for the operand reads)
+    const uint8_t *k8base = QK8 ? p.k8 + ((int64_t)b * p.hkv + g) * p.mkv * (int64_t)(BN * D) : nullptr;
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = VT ? (int64_t)(BN * D) : (int64_t)BN * p.vsn;
     auto copy_k = [&](int t, uint32_t dst) {              // K_t into the ring slot at LDS byte address dst
-        if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
-        else tile_copy_async<D, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
+        if constexpr (QK8) {
+            tile_copy_async<NSTK, NT>(k8base + (int64_t)t * (BN * D), koff, dst, wave);       // (padded already)
+        } else {
+            if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
+            else tile_copy_async<NSTK, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
+        }
     };
     auto copy_v = [&](int t) {                            // V_t into slot t & 1
         const uint32_t dst = lds_v0 + (uint32_t)(t & 1) * TILE_BYTES;
         if (!VT && t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave);
-        else tile_copy_async<D, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);   // (workspace tiles are padded already)
+        else tile_copy_async<NST, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);   // (workspace tiles are padded already)
     };
 
     // Operand gather addresses (bytes inside a tile slot).
     // K (A operand of S^T): lane reads key row 32*kb + l32, chunk (2s + hh) ^ swz_k(row).  The row
     // swizzle does not depend on kb (32 is a multiple of its period) and 2s only occupies chunk
     // bits 1.., so  addr(s, kb) = (ka_base ^ (s << 5)) + kb * 32 * ROW_BYTES.
-    const uint32_t ka_base = (uint32_t)(l32 * ROW_BYTES + ((hh ^ swz_k<D>(l32)) << 4));
+    // QK8: the tile holds fp8, 64 rows of 128 bytes, chunk index XOR-ed with (row >> 1) & 7; a lane
+    // reads row 32*kb + l32, head-dim bytes 64s + 32hh .. +31 as two b128 (chunks 4s + 2hh + {0, 1}):
+    // addr(s, kb, e) = (ka_base ^ (s << 6) ^ (e << 4)) + kb * 32 * 128.
+    const uint32_t ka_base = QK8 ? (uint32_t)(l32 * 128 + (((2 * hh) ^ ((l32 >> 1) & 7)) << 4))
+                                 : (uint32_t)(l32 * ROW_BYTES + ((hh ^ swz_k<D>(l32)) << 4));
     // V (A operand of O^T, transposing read of 4 keys x 16 head-dim columns per 16 lanes): lane
     // reads row 16u + 4hh + (L >> 2) (+8 for the second half), 8 bytes.  Which head-dim column an
     // operand row stands for is free (it only permutes the rows of O^T, undone at the final
@@ -153,13 +165,37 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                                 : (uint32_t)(vrow * ROW_BYTES + (((vcol >> 3) ^ swz_v<D>(vrow)) << 4) + ((vcol >> 2) & 1) * 8);
 
     // Q_i^T as the B operand: lane holds query (32*wrow + l32), head-dim slice 16s + 8hh .. +7
-    bf16x8 qreg[KS];
+    // (QK8: slice 64s + 32hh .. +31, rounded to fp8 here, once)
+    constexpr int KSQ = QK8 ? D / 64 : KS;               // score MFMA k-steps
+    constexpr int NQK = 2 * KSQ;                         // score MFMAs per block: (k-step, 32-key half)
+    typedef std::conditional_t<QK8, i32x8, bf16x8> kop_t; // one score operand
+    kop_t qreg[KSQ];
     const int q_row = (int)row0 + wrow * 32 + l32;
     {
-        const uint16_t *qp = p.q + (int64_t)b * p.qsb + (int64_t)min(q_row, n_tok - 1) * p.qsn + (int64_t)h * p.qsh + 8 * hh;
+        const uint16_t *qrow = p.q + (int64_t)b * p.qsb + (int64_t)min(q_row, n_tok - 1) * p.qsn + (int64_t)h * p.qsh;
+        if constexpr (QK8) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+            for (int s = 0; s < KSQ; ++s)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bf16x8 v8 = *reinterpret_cast<const bf16x8 *>(qrow + 64 * s + 32 * hh + 8 * c);
+                    float f[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = (float)v8[e];
+                    int w0, w1;
+                    cvt8_fp8(f, w0, w1);
+                    qreg[s][2 * c] = w0;
+                    qreg[s][2 * c + 1] = w1;
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8 *>(qrow + 8 * hh + 16 * s);
+        }
     }
+    auto qk_mma = [&](const kop_t &a, const kop_t &b, f32x16 c) {
+        if constexpr (QK8) return mfma64_fp8(a, b, c);
+        else return mfma16(a, b, c);
+    };
 
     f32x16 oacc[DB];
 #pragma unroll
@@ -176,10 +212,18 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // K operand n (= k-step n/2, 32-key half n%2) of the tile at LDS byte address kaddr (+ka_base)
     auto k_operand = [&](uint32_t kaddr, int n) {
-        const uint32_t a_s = kaddr ^ (uint32_t)((n >> 1) << 5);
-        return *LDS_PTR(const bf16x8, a_s + (n & 1) * 32 * ROW_BYTES);
+        if constexpr (QK8) {
+            const uint32_t a_s = (kaddr ^ (uint32_t)((n >> 1) << 6)) + (n & 1) * 32 * 128;
+            const i32x4 lo = *LDS_PTR(const i32x4, a_s);
+            const i32x4 hi = *LDS_PTR(const i32x4, a_s ^ 16u);
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        } else {
+            const uint32_t a_s = kaddr ^ (uint32_t)((n >> 1) << 5);
+            return *LDS_PTR(const bf16x8, a_s + (n & 1) * 32 * ROW_BYTES);
+        }
     };
     constexpr int PD = 4;            // LDS operand reads are issued PD MFMAs ahead of their use
+    constexpr int PDK = QK8 ? 2 : PD; // ... of the score operands (the fp8 ones are twice as wide and four in all)
 
     // S^T of block j from the K tile at LDS byte address `kt` (MFMA and LDS reads only); the
     // order reads-ahead / MFMA is pinned so that no MFMA waits for a read issued just before it
@@ -189,14 +233,14 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 #pragma unroll
             for (int e = 0; e < 16; ++e) t.s[kb][e] = 0.f;
         const uint32_t kaddr = kt + ka_base;
-        bf16x8 a[2 * KS + PD];
+        kop_t a[NQK + PDK];
 #pragma unroll
-        for (int n = 0; n < PD; ++n) a[n] = k_operand(kaddr, n);
+        for (int n = 0; n < PDK; ++n) a[n] = k_operand(kaddr, n);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int n = 0; n < 2 * KS; ++n) {
-            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
-            t.s[n & 1] = mfma16(a[n], qreg[n >> 1], t.s[n & 1]);
+        for (int n = 0; n < NQK; ++n) {
+            if (n + PDK < NQK) a[n + PDK] = k_operand(kaddr, n + PDK);
+            t.s[n & 1] = qk_mma(a[n], qreg[n >> 1], t.s[n & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -297,15 +341,15 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // the VALU run together.  K operands are read PD MFMAs ahead.
     auto fused_exp_qk = [&](ScoreTile &cur, ScoreTile &nxt, uint32_t kt, float m_use, float alpha, bf16x8 (&pb)[4]) {
         const uint32_t kaddr = kt + ka_base;
-        bf16x8 a[2 * KS + PD];
+        kop_t a[NQK + PDK];
 #pragma unroll
-        for (int n = 0; n < PD; ++n) a[n] = k_operand(kaddr, n);
+        for (int n = 0; n < PDK; ++n) a[n] = k_operand(kaddr, n);
         float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) nxt.s[kb][e] = 0.f;
-        constexpr int EPM = 32 / (2 * KS);         // exponentials per MFMA (2 at D = 128, 4 at D = 64)
+        constexpr int EPM = 32 / NQK;              // exponentials per MFMA (2 at D = 128, 4 at D = 64; 8 with fp8 operands)
         // The exponentials of one MFMA slot are rounded, packed and summed one slot later, so that
         // no instruction waits for a transcendental issued just before it.
         float ex[EPM];
@@ -322,9 +366,9 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             }
         };
 #pragma unroll
-        for (int n = 0; n < 2 * KS; ++n) {
-            if (n + PD < 2 * KS) a[n + PD] = k_operand(kaddr, n + PD);
-            nxt.s[n & 1] = mfma16(a[n], qreg[n >> 1], nxt.s[n & 1]);
+        for (int n = 0; n < NQK; ++n) {
+            if (n + PDK < NQK) a[n + PDK] = k_operand(kaddr, n + PDK);
+            nxt.s[n & 1] = qk_mma(a[n], qreg[n >> 1], nxt.s[n & 1]);
             float nx[EPM];
 #pragma unroll
             for (int t = 0; t < EPM; ++t) {
@@ -336,7 +380,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             for (int t = 0; t < EPM; ++t) ex[t] = nx[t];
             __builtin_amdgcn_sched_barrier(0);
         }
-        pack(2 * KS - 1);
+        pack(NQK - 1);
         l_run = l_run * alpha + (psum0 + psum1);
     };
 
@@ -409,8 +453,8 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         // copies that must have landed before the barrier: V_j (if requested) and K_{j+2}; every
         // younger request (K_{j+3} .. K_{j+R-1}, issued after V_j) may stay in flight
         if (R >= 4 && j - 1 + R < n_blk) {
-            if (!CALIB && cur.any_keep) wait_vmcnt<NST>();
-            else wait_vmcnt<(R >= 4 ? NST * (R - 3) : 0)>();
+            if (!CALIB && cur.any_keep) wait_vmcnt<NSTK>();
+            else wait_vmcnt<(R >= 4 ? NSTK * (R - 3) : 0)>();
         } else {
             wait_vmcnt<0>();
         }
@@ -431,7 +475,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                 decide(nxt, j + 1, red, fast_tag);
                 if (!CALIB && nxt.keep) softmax_begin(nxt);   // running max and rescale factor, off the critical path
                 if (!CALIB && nxt.any_keep) {
-                    if constexpr (FAST) tile_copy_async<D, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
+                    if constexpr (FAST) tile_copy_async<NST, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
                     else copy_v(j + 1);                   // a gateable block is never the partial one
                 }
                 if (j + R < n_blk) copy_k(j + R, kt_next);
@@ -569,13 +613,49 @@ __global__ void __launch_bounds__(256) transpose_v_kernel(const FwdParams p)
     }
 }
 
-template <int D, int NWH, int HP, int KR, bool F16, bool VT>
+// K -> workspace as fp8 (e4m3, round to nearest even), once per call, for the fp8 score product: for
+// every (batch, KV head, 64-key block) a tile of 64 rows x 128 bytes in the byte order the forward
+// kernel wants in LDS (16-byte chunk index XOR-ed with (row >> 1) & 7).  Rows at and beyond the
+// sequence end repeat the last token (Section 4.3).  head_dim 128 only.
+template <bool F16>
+__global__ void __launch_bounds__(256) quantize_k_kernel(const FwdParams p)
+{
+    typedef typename Elem<F16>::x8 x8;
+    constexpr int BN = kBlockN, D = 128;
+    const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    int n_tok = p.seqlen;
+    if (p.seqlens) n_tok = min(max(p.seqlens[b], 0), p.seqlen);
+    if (j * BN >= n_tok) return;
+    const uint16_t *src = p.k + (int64_t)b * p.ksb + (int64_t)g * p.ksh;
+    uint8_t *dst = p.k8 + (((int64_t)b * p.hkv + g) * p.mkv + j) * (int64_t)(BN * D);
+    for (int sigma = tid; sigma < BN * 8; sigma += 256) {
+        const int row = sigma >> 3, cphys = sigma & 7;
+        const int c = cphys ^ ((row >> 1) & 7);               // head-dim elements 16c .. 16c + 15
+        const int tok = min(j * BN + row, n_tok - 1);
+        const uint16_t *e = src + (int64_t)tok * p.ksn + 16 * c;
+        i32x4 o;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const x8 v8 = *reinterpret_cast<const x8 *>(e + 8 * half);
+            float f[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) f[t] = (float)v8[t];
+            int w0, w1;
+            cvt8_fp8(f, w0, w1);
+            o[2 * half] = w0;
+            o[2 * half + 1] = w1;
+        }
+        *reinterpret_cast<i32x4 *>(dst + (int64_t)sigma * 16) = o;
+    }
+}
+
+template <int D, int NWH, int HP, int KR, bool F16, bool VT, bool QK8>
 static hipError_t launch_k(const FwdParams &p, bool calib, hipStream_t stream, long grid)
 {
     if (calib)
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true, F16, false>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, true, F16, false, QK8>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     else
-        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false, F16, VT>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
+        hipLaunchKernelGGL((bsfa_fwd_kernel<D, NWH, HP, KR, false, F16, VT, QK8>), dim3((unsigned)grid), dim3(NWH * HP * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -590,16 +670,29 @@ static hipError_t launch_t(const FwdParams &p, bool calib, hipStream_t stream)
         const int n = p.batch * p.hq * 3;
         hipLaunchKernelGGL(zero_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p.counts, n);
     }
-    if constexpr (NWH == 4) {          // the 128-row tile can take V from the transposed workspace
-        if (p.vt && !calib) {
+    if constexpr (NWH == 4) {          // the 128-row tile can take V (and fp8 K) from the workspace
+        if (p.k8 && !calib && !p.vt) return hipErrorInvalidValue;   // the fp8 score path always takes V from the workspace
+        if ((p.vt && !calib) || p.k8) {
             if (p.hkv > 65535 || p.batch > 65535) return hipErrorInvalidValue;    // grid y, z limits
-            hipLaunchKernelGGL((transpose_v_kernel<D>), dim3((unsigned)p.mkv, (unsigned)p.hkv, (unsigned)p.batch), dim3(256), 0, stream, p);
+            const dim3 tiles((unsigned)p.mkv, (unsigned)p.hkv, (unsigned)p.batch);
+            if (p.vt && !calib) hipLaunchKernelGGL((transpose_v_kernel<D>), tiles, dim3(256), 0, stream, p);
+            if constexpr (D == 128) {
+                if (p.k8) {
+                    if (p.f16) hipLaunchKernelGGL((quantize_k_kernel<true>), tiles, dim3(256), 0, stream, p);
+                    else hipLaunchKernelGGL((quantize_k_kernel<false>), tiles, dim3(256), 0, stream, p);
+                    hipError_t e = hipGetLastError();
+                    if (e != hipSuccess) return e;
+                    return p.f16 ? launch_k<D, NWH, HP, KR, true, true, true>(p, calib, stream, grid)
+                                 : launch_k<D, NWH, HP, KR, false, true, true>(p, calib, stream, grid);
+                }
+            }
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            return p.f16 ? launch_k<D, NWH, HP, KR, true, true>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, true>(p, calib, stream, grid);
+            return p.f16 ? launch_k<D, NWH, HP, KR, true, true, false>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, true, false>(p, calib, stream, grid);
         }
     }
-    return p.f16 ? launch_k<D, NWH, HP, KR, true, false>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, false>(p, calib, stream, grid);
+    if (p.k8) return hipErrorInvalidValue;             // fp8 score operands need the 128 x 64 tile and head_dim 128
+    return p.f16 ? launch_k<D, NWH, HP, KR, true, false, false>(p, calib, stream, grid) : launch_k<D, NWH, HP, KR, false, false, false>(p, calib, stream, grid);
 }
 
 bool shape_supported(int head_dim, int block_m, int block_n)

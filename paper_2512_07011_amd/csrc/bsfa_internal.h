@@ -14,6 +14,8 @@ struct FwdParams {
     uint16_t *vt;                    // workspace for the transposed V tiles ([batch][hkv][mkv] tiles of 64 x head_dim
                                      // elements), or null: V is then gathered with transposing LDS reads
     const float *tau;                // [hq] or [hq][tau_tiles]
+    uint8_t *k8;                     // workspace for K as fp8 tiles ([batch][hkv][mkv] tiles of 64 x 128 bytes), or null:
+                                     // the score product then runs on the 16-bit elements
     const int32_t *seqlens;          // [batch] tokens per batch element, or null (all have seqlen)
     int64_t qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;
     int batch, hq, hkv, group, seqlen, mq, mkv;

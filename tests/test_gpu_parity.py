@@ -381,3 +381,45 @@ def test_running_max_predicate_matches_algorithm(oracle):
     assert kept_gate > 5                                  # and some gateable blocks behind the first survive
     with pytest.raises(binding.BsfaError):
         binding.bsfa_forward(qd, kd, vd, lam_d, gate_mode=2)
+
+
+def _to_e4m3(t):
+    """Round to fp8 e4m3 (nearest even) and widen back: every value is then exact in bf16."""
+    return t.to(torch.float8_e4m3fn).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("hq,hkv,n", [(4, 2, 1024), (6, 2, 870)])
+def test_fp8_score_product(oracle, hq, hkv, n):
+    """qk_fp8: the score product runs on fp8 (e4m3) copies of Q and K.  The kernel's rounding is round to
+    nearest even, so on bf16 inputs it must agree with the oracle fed Q and K rounded the same way by
+    torch (block maxima to 1e-4, masks outside the band, outputs within the usual tolerances), and on
+    inputs that already are fp8 values it changes nothing about what is compared.  Paired and single
+    heads, ragged length, dense and gated, thresholds from bsfa_calibrate in the same mode."""
+    shp = synth.Shape(1, 1024, hq, hkv, 128, 128, 64)
+    q, k, v = (t.to(torch.bfloat16).to(DEV) for t in synth.tiny(91, shp, n_boost=5))
+    q, k, v = (t[:, :n].contiguous() for t in (q, k, v))
+    q8, k8 = _to_e4m3(q), _to_e4m3(k)
+    assert not torch.equal(q8, q)
+    tau = binding.bsfa_calibrate(q, k, [0.5], qk_fp8=True)[0]
+    # calibration in fp8 mode = order statistic of the fp8-rounded problem's block maxima (the 16-bit
+    # product of the same values sums in another order: equal to rounding)
+    tau_ref = binding.bsfa_calibrate(q8, k8, [0.5])[0]
+    assert torch.allclose(tau, tau_ref, rtol=0, atol=3e-4)
+    neg = torch.full((hq,), float("-inf"))
+    for thr in (neg, tau):
+        for inputs in ((q, k), (q8, k8)):
+            st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True, block_max=True, lse=True)
+            out = binding.bsfa_forward(inputs[0], inputs[1], v, thr.to(DEV), skip_stats=st, qk_fp8=True)
+            torch.cuda.synchronize()
+            rep = parity.compare(q8, k8, v, thr, 128, 64, True, out, st.skip_mask, st.block_max, lse_gpu=st.lse)
+            assert rep.mask_mismatch <= rep.in_band
+        if thr is tau:
+            assert rep.skipped > 0
+    # and the 16-bit path on the rounded inputs gives the same masks (same scores up to summation order)
+    st2 = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    binding.bsfa_forward(q8, k8, v, tau.to(DEV), skip_stats=st2)
+    torch.cuda.synchronize()
+    assert (st2.counts[..., 0] - st.counts[..., 0]).abs().sum() <= rep.in_band
+    with pytest.raises(binding.BsfaError) as e:
+        binding.bsfa_forward(q, k, v, tau.to(DEV), qk_fp8=True, workspace=None)
+    assert e.value.status == -5
