@@ -7,6 +7,7 @@
 #include <math.h>
 
 #include <type_traits>
+#include <utility>
 
 namespace bsfa {
 
@@ -174,6 +175,18 @@ __device__ __forceinline__ float wave_max_paired(float x)
     const int xi = __builtin_bit_cast(int, x);
     return fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)),
                  __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16)));
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order: a fully unrolled loop
+// whose body sees its index as a constant expression
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
 // Work decomposition: a work item is (batch b, KV head, group of HP query heads, query tile i).

@@ -34,6 +34,7 @@ struct ScoreTile {
     bool any_keep;        // some head of the workgroup keeps the block (workgroup-uniform): V is fetched
     float m_use;          // kept blocks: row max the exponentials are taken against (log2 units)
     float alpha;          // kept blocks: factor that rescales the running accumulator and normaliser
+    bool resc;            // kept blocks: alpha differs from 1 in some lane of the wave
 };
 
 template <int D, int NWH, int HP, int KR, bool CALIB, bool F16, bool VT, bool QK8>
@@ -110,6 +111,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         tau_h[x] = CALIB ? -INFINITY      // the score half takes no decisions
                          : p.tau[p.tau_per_tile ? (int64_t)(h0 + x) * p.tau_tiles + min(i, p.tau_tiles - 1) : (h0 + x)];
 
+    const float tau_own = hsel ? tau_h[HP - 1] : tau_h[0];
     uint32_t koff[NSTK], voff[NST];
 #pragma unroll
     for (int r = 0; r < NST; ++r) {
@@ -119,19 +121,26 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // QK8: K comes from the workspace as fp8 tiles (64 rows of D bytes, swizzled for the operand reads)
     const uint8_t *k8base = QK8 ? p.k8 + ((int64_t)b * p.hkv + g) * p.mkv * (int64_t)(BN * D) : nullptr;
     const int64_t kstep = (int64_t)BN * p.ksn, vstep = VT ? (int64_t)(BN * D) : (int64_t)BN * p.vsn;
-    auto copy_k = [&](int t, uint32_t dst) {              // K_t into the ring slot at LDS byte address dst
+    // K_t, whose first row is at `src`, into the ring slot at LDS byte address dst
+    auto copy_k_from = [&](const unsigned char *src, int t, uint32_t dst) {
         if constexpr (QK8) {
-            tile_copy_async<NSTK, NT>(k8base + (int64_t)t * (BN * D), koff, dst, wave);       // (padded already)
+            tile_copy_async<NSTK, NT>(src, koff, dst, wave);                                  // (padded already)
         } else {
-            if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(kbase + (int64_t)t * kstep, (int)p.ksn, partial_rows, dst, wave);
-            else tile_copy_async<NSTK, NT>(kbase + (int64_t)t * kstep, koff, dst, wave);
+            if (t == partial_blk) tile_copy_async_clamped<D, NT, false>(reinterpret_cast<const uint16_t *>(src), (int)p.ksn, partial_rows, dst, wave);
+            else tile_copy_async<NSTK, NT>(src, koff, dst, wave);
         }
     };
-    auto copy_v = [&](int t) {                            // V_t into slot t & 1
+    // V_t, whose first row is at `src`, into slot t & 1
+    auto copy_v_from = [&](const unsigned char *src, int t) {
         const uint32_t dst = lds_v0 + (uint32_t)(t & 1) * TILE_BYTES;
-        if (!VT && t == partial_blk) tile_copy_async_clamped<D, NT, true>(vbase + (int64_t)t * vstep, (int)p.vsn, partial_rows, dst, wave);
-        else tile_copy_async<NST, NT>(vbase + (int64_t)t * vstep, voff, dst, wave);   // (workspace tiles are padded already)
+        if (!VT && t == partial_blk) tile_copy_async_clamped<D, NT, true>(reinterpret_cast<const uint16_t *>(src), (int)p.vsn, partial_rows, dst, wave);
+        else tile_copy_async<NST, NT>(src, voff, dst, wave);                                  // (workspace tiles are padded already)
     };
+    const unsigned char *const k_bytes = QK8 ? reinterpret_cast<const unsigned char *>(k8base) : reinterpret_cast<const unsigned char *>(kbase);
+    const unsigned char *const v_bytes = reinterpret_cast<const unsigned char *>(vbase);
+    const int64_t kstep_b = QK8 ? (int64_t)(BN * D) : kstep * 2, vstep_b = vstep * 2;      // bytes from one tile to the next
+    auto copy_k = [&](int t, uint32_t dst) { copy_k_from(k_bytes + t * kstep_b, t, dst); };
+    auto copy_v = [&](int t) { copy_v_from(v_bytes + t * vstep_b, t); };
 
     // Operand gather addresses (bytes inside a tile slot).
     // K (A operand of S^T): lane reads key row 32*kb + l32, chunk (2s + hh) ^ swz_k(row).  The row
@@ -224,6 +233,13 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     };
     constexpr int PD = 4;            // LDS operand reads are issued PD MFMAs ahead of their use
     constexpr int PDK = QK8 ? 2 : PD; // ... of the score operands (the fp8 ones are twice as wide and four in all)
+    // The first PDK score operands of a block are read one phase early (at the end of the previous
+    // stage, behind its last MFMAs), so that the score MFMAs do not start with an LDS round trip.
+    kop_t kpre[PDK];
+    auto prefetch_k = [&](uint32_t kt) {
+#pragma unroll
+        for (int n = 0; n < PDK; ++n) kpre[n] = k_operand(kt + ka_base, n);
+    };
 
     // S^T of block j from the K tile at LDS byte address `kt` (MFMA and LDS reads only); the
     // order reads-ahead / MFMA is pinned so that no MFMA waits for a read issued just before it
@@ -235,7 +251,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const uint32_t kaddr = kt + ka_base;
         kop_t a[NQK + PDK];
 #pragma unroll
-        for (int n = 0; n < PDK; ++n) a[n] = k_operand(kaddr, n);
+        for (int n = 0; n < PDK; ++n) a[n] = kpre[n];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int n = 0; n < NQK; ++n) {
@@ -247,8 +263,24 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
 
     // causal mask on boundary blocks, row maxima, and the wave's block maximum into
     // lds_red[j & 1].  FAST: the block is known to be gateable (no causal mask).
+    // FAST in the forward kernel proper: nobody asks for the maximum itself, only for the decision,
+    // and  max_lanes(m) * c >= T  <=>  some lane has m * c >= T  (c > 0, rounding is monotone): every
+    // lane compares its own maximum with its head's threshold and the wave publishes one flag.  That
+    // takes the cross-lane reductions out of the stretch between the last score MFMA and the barrier,
+    // where nothing else runs; the row maximum the softmax needs is completed after the barrier.
     auto reduce_scores = [&](ScoreTile &t, int j, auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
+        if constexpr (FAST && !CALIB) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, t.s[kb][e]);
+            t.mx = mx;                                        // this lane's half of the row; see finish_row_max
+            const bool wave_ge = __builtin_amdgcn_ballot_w64(mx * p.scale >= tau_own) != 0ull;
+            if (lane == 0) lds_red[j & 1][wave] = wave_ge ? 1.f : 0.f;
+            return;
+        }
         const bool gated = FAST ? true : is_gated(j);
         if constexpr (!FAST) {
             if (p.causal && !gated) {
@@ -319,6 +351,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const float m_new = fmaxf(m_run, t.mx * p.scale_log2);
         t.m_use = (m_new == -INFINITY) ? 0.f : m_new;
         t.alpha = __builtin_amdgcn_exp2f(m_run - t.m_use);
+        t.resc = __builtin_amdgcn_ballot_w64(t.alpha != 1.0f) != 0ull;
         m_run = m_new;
     };
     auto softmax_exp = [&](ScoreTile &t, float m_use, float alpha, bf16x8 (&pb)[4]) {
@@ -343,7 +376,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         const uint32_t kaddr = kt + ka_base;
         kop_t a[NQK + PDK];
 #pragma unroll
-        for (int n = 0; n < PDK; ++n) a[n] = k_operand(kaddr, n);
+        for (int n = 0; n < PDK; ++n) a[n] = kpre[n];
         float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -384,21 +417,22 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         l_run = l_run * alpha + (psum0 + psum1);
     };
 
-    auto rescale = [&](float alpha) {
-        if (__any(alpha != 1.0f)) {
+    auto rescale = [&](const ScoreTile &t) {
+        if (t.resc) {
 #pragma unroll
             for (int x = 0; x < DB; ++x)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[x][e] *= alpha;
+                for (int e = 0; e < 16; ++e) oacc[x][e] *= t.alpha;
         }
     };
 
     // O^T += V^T P^T for the V tile at LDS byte address `vt`; operand n = (k-step u = n / DB,
     // head-dim block x = n % DB), read PD MFMAs ahead
-    // `mid` runs after the first PV_MID MFMAs have been issued (work that only has to happen
-    // soon after the barrier goes there, beside the matrix pipe instead of in front of it)
-    constexpr int PV_MID = 6;
-    auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt, auto mid) {
+    // `hook(n)` runs after MFMA n has been issued (n a compile-time constant): work that only has to
+    // happen soon after the barrier goes there in small pieces, beside the matrix pipe instead of in
+    // front of it
+    constexpr int NPV = 4 * DB;
+    auto pv = [&](const bf16x8 (&pb)[4], uint32_t vt, auto hook) {
         const uint32_t vaddr = vt + va_base;
         auto v_operand = [&](int n) {
             const int u = n / DB, x = n % DB;
@@ -409,27 +443,29 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, av);
         };
-        bf16x8 a[4 * DB + PD];
+        bf16x8 a[NPV + PD];
 #pragma unroll
         for (int n = 0; n < PD; ++n) a[n] = v_operand(n);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int n = 0; n < 4 * DB; ++n) {
-            if (n + PD < 4 * DB) a[n + PD] = v_operand(n + PD);
+        static_for<NPV>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            if constexpr (n + PD < NPV) a[n + PD] = v_operand(n + PD);
             oacc[n % DB] = mfma16(a[n], pb[n / DB], oacc[n % DB]);
             __builtin_amdgcn_sched_barrier(0);
-            if (n == PV_MID - 1) {
-                mid();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+            hook(nc);
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     uint32_t kring = (uint32_t)(1 % KR) * TILE_BYTES;     // ring offset of the K slot the next stage reads
+    // sources of the copies a stage requests, advanced by one block per stage: K_{j+R} and V_{j+1}
+    const unsigned char *k_ahead = k_bytes + R * kstep_b;
+    const unsigned char *v_ahead = v_bytes + vstep_b;
     // One pipeline stage: finish block j (`cur`), look ahead to block j+1 (`nxt`).
     // FAST: block j+1 exists and is gateable, so the look-ahead has no mask and no conditionals.
     auto stage = [&](ScoreTile &cur, ScoreTile &nxt, int j, auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
+        constexpr bool FLAGS = FAST && !CALIB;           // the waves publish decisions, not maxima (see reduce_scores)
         const bool has_next = FAST || (j + 1 < n_blk);
         bf16x8 pb[4];
         const bool do_pv = !CALIB && cur.keep;
@@ -437,13 +473,15 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         // (R = KR + 1), so one ring position per stage is all the bookkeeping there is
         const uint32_t kt_next = lds_k0 + kring;
         kring = (kring + TILE_BYTES == KR * TILE_BYTES) ? 0u : kring + TILE_BYTES;
+        const unsigned char *const k_src = k_ahead, *const v_src = v_ahead;
+        k_ahead += kstep_b;
+        v_ahead += vstep_b;
         if (do_pv) {
-            const float m_use = cur.m_use, alpha = cur.alpha;
-            rescale(alpha);                       // the previous block's PV has been issued already
+            rescale(cur);                         // the previous block's PV has been issued already
             if constexpr (FAST) {
-                fused_exp_qk(cur, nxt, kt_next, m_use, alpha, pb);
+                fused_exp_qk(cur, nxt, kt_next, cur.m_use, cur.alpha, pb);
             } else {
-                softmax_exp(cur, m_use, alpha, pb);
+                softmax_exp(cur, cur.m_use, cur.alpha, pb);
                 if (has_next) qk_mfma(nxt, kt_next);
             }
         } else {
@@ -465,26 +503,76 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
             for (int w = 0; w < NW; ++w) red[w] = lds_red[(j + 1) & 1][w];
         }
         __builtin_amdgcn_sched_barrier(0);
-        // decision for block j+1, then the requests for V_{j+1} and K_{j+R}
-        auto look_ahead = [&]() {
-            if (has_next) {
-                // the maxima are consumed here and not earlier: nothing computed from them may be
-                // hoisted in front of the PV MFMAs, where it would wait for the LDS read
+        // The look-ahead -- decision for block j+1, its statistics, the requests for V_{j+1} and
+        // K_{j+R}, the running maximum -- in pieces, so that a kept block can issue them between its
+        // PV MFMAs a few instructions at a time.
+        auto la_decide = [&]() {
+            if (!has_next) return;
+            // the maxima are consumed here and not earlier: nothing computed from them may be
+            // hoisted in front of the PV MFMAs, where it would wait for the LDS read
 #pragma unroll
-                for (int w = 0; w < NW; ++w) asm volatile("" : "+v"(red[w]));
-                decide(nxt, j + 1, red, fast_tag);
-                if (!CALIB && nxt.keep) softmax_begin(nxt);   // running max and rescale factor, off the critical path
-                if (!CALIB && nxt.any_keep) {
-                    if constexpr (FAST) tile_copy_async<NST, NT>(vbase + (int64_t)(j + 1) * vstep, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
-                    else copy_v(j + 1);                   // a gateable block is never the partial one
+            for (int w = 0; w < NW; ++w) asm volatile("" : "+v"(red[w]));
+            if constexpr (FLAGS) {
+                bool kx[HP];
+#pragma unroll
+                for (int x = 0; x < HP; ++x) {
+                    float f = red[x * NWH];
+#pragma unroll
+                    for (int w = 1; w < NWH; ++w) f = fmaxf(f, red[x * NWH + w]);
+                    kx[x] = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, f)) != 0;   // a scalar: the branches below are uniform
                 }
-                if (j + R < n_blk) copy_k(j + R, kt_next);
+                const bool keep = hsel ? kx[HP - 1] : kx[0];
+                nxt.keep = keep;
+                nxt.any_keep = kx[0] || kx[HP - 1];
+                n_skipped += keep ? 0 : 1;
+                mask_word |= (keep ? 0u : 1u) << ((j + 1) & 31);
+            } else {
+                decide(nxt, j + 1, red, fast_tag);
+            }
+        };
+        auto la_stats = [&]() {
+            if constexpr (FLAGS) {                        // (block j+1 is never the tile's last one here)
+                if (((j + 1) & 31) == 31) {
+                    if (p.skip_mask && stat_lane) p.skip_mask[stat_row * p.mask_words + ((j + 1) >> 5)] = mask_word;
+                    mask_word = 0;
+                }
+            }
+        };
+        auto la_vcopy = [&]() {
+            if (has_next && !CALIB && nxt.any_keep) {
+                if constexpr (FAST) tile_copy_async<NST, NT>(v_src, voff, lds_v0 + (uint32_t)((j + 1) & 1) * TILE_BYTES, wave);
+                else copy_v_from(v_src, j + 1);           // a gateable block is never the partial one
+            }
+        };
+        auto la_kcopy = [&]() {
+            if (has_next && j + R < n_blk) copy_k_from(k_src, j + R, kt_next);
+        };
+        auto la_softmax = [&]() {                        // running max and rescale factor, off the critical path
+            if (has_next && !CALIB && nxt.keep) {
+                if constexpr (FLAGS) nxt.mx = pair_max(nxt.mx);
+                softmax_begin(nxt);
             }
         };
         if (do_pv) {
-            if constexpr (!CALIB) pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES, look_ahead);
+            if constexpr (!CALIB) {
+                constexpr int HS = NPV / 8;               // MFMAs from one piece to the next
+                pv(pb, lds_v0 + (uint32_t)(j & 1) * TILE_BYTES, [&](auto nc) {
+                    constexpr int n = decltype(nc)::value;
+                    if constexpr (n == HS) la_decide();
+                    if constexpr (n == 2 * HS) la_stats();
+                    if constexpr (n == 3 * HS) la_vcopy();
+                    if constexpr (n == 4 * HS) la_kcopy();
+                    if constexpr (n == 5 * HS) la_softmax();
+                    if constexpr (n == NPV - 2) prefetch_k(lds_k0 + kring);   // K_{j+2}: landed and visible since the barrier
+                });
+            }
         } else {
-            look_ahead();
+            la_decide();
+            la_stats();
+            la_vcopy();
+            la_kcopy();
+            la_softmax();
+            prefetch_k(lds_k0 + kring);
         }
     };
 
@@ -493,6 +581,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     copy_k(0, lds_k0);
     wait_vmcnt<0>();
     wg_barrier();
+    prefetch_k(lds_k0);
     qk_mfma(ta, lds_k0);
     reduce_scores(ta, 0, std::false_type{});
     wg_barrier();                                       // block maxima visible, K_0 consumed
@@ -509,6 +598,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
         if (t < n_blk) copy_k(t, lds_k0 + (uint32_t)(t % KR) * TILE_BYTES);
     wait_vmcnt<0>();                                       // drained once; from here on the steady-state rule holds
     wg_barrier();
+    prefetch_k(lds_k0 + kring);                            // K_1 for the first stage
 
     // main loop, two stages per trip.  A pair runs the fused, mask-free stages when both of its
     // look-ahead blocks (j+1, j+2) exist and are gateable: every pair below the causal boundary;
@@ -517,7 +607,7 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
     // gate).  The remaining pairs take the general stages.
     int j = 0;
     for (int seg = 0; seg < 2; ++seg) {
-        const int fast_end = p.gate_mode ? 0 : seg == 0 ? (p.causal ? n_gate : own_lo) : (p.causal ? 0 : n_blk);
+        const int fast_end = (p.gate_mode || (!CALIB && p.block_max)) ? 0 : seg == 0 ? (p.causal ? n_gate : own_lo) : (p.causal ? 0 : n_blk);
         for (; j + 2 < fast_end; j += 2) {
             stage(ta, tb, j, std::true_type{});
             stage(tb, ta, j + 1, std::true_type{});
