@@ -20,6 +20,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -27,6 +28,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz)
+NOMINAL_SCLK_MHZ = 2400.0      # the shader clock that peak is quoted at
 
 
 def main():
@@ -43,6 +45,8 @@ def main():
                     help="comma-separated extra sequence lengths timed at --skip and dense ('' for none): adds a 'sizes' list")
     ap.add_argument("--noncausal", type=int, default=32768,
                     help="sequence length of the bidirectional leg (causal = 0; dense and --skip); 0 for none")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the probe of the matrix rate the card sustains (back-to-back MFMAs, nothing else)")
     ap.add_argument("--no-fp8-leg", action="store_true",
                     help="skip the leg that runs the score product on fp8 copies of Q and K (dense and --skip at --seqlen)")
     ap.add_argument("--no-cpu", action="store_true", help="skip every CPU-oracle leg (baseline and per-point parity)")
@@ -75,7 +79,7 @@ def main():
         from tests import parity
         orc.build()
 
-    def measure(seqlen, targets, steps, warmup, parity_budget, causal=True, qk_fp8=False):
+    def measure(seqlen, targets, steps, warmup, parity_budget, causal=True, qk_fp8=False, want_sclk=False):
         """Dense path and every skip target at one sequence length.  Returns (shape, tensors, thresholds,
         list of point records); the first record is the dense path."""
         shp = synth.llama_shape(seqlen, block_m=bm)
@@ -115,6 +119,23 @@ def main():
             t_wall = time.perf_counter() - t_wall
             per = [ev[s].elapsed_time(ev[s + 1]) for s in range(steps)]   # ms on the launch stream (incl. the small side kernels)
             return t_wall * 1e3 / steps, per, st.counts.cpu().numpy().copy()
+
+        def sclk(thr):
+            """Shader clock (MHz) that the management interface reports while this launch keeps the GPU busy
+            (outside the timed region); None if it cannot be read."""
+            for _ in range(max(4, int(1500.0 / max(ms_dense or 100.0, 1.0)))):
+                fwd(thr, st)
+            time.sleep(0.4)
+            mhz = None
+            try:
+                r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
+                for line in r.stdout.splitlines():
+                    if "sclk" in line and "Mhz" in line:
+                        mhz = int(line.split("(")[-1].split("Mhz")[0])
+            except Exception:
+                mhz = None
+            torch.cuda.synchronize()
+            return mhz
 
         def check(thr_host, thr_dev, budget, n_random):
             """Sampled oracle parity of the launch just timed (block budget bounds the CPU time)."""
@@ -163,6 +184,11 @@ def main():
                    "flops_per_launch": f_exec,
                    "speedup_vs_own_dense": round(ms_dense / ms, 4), "ideal_speedup": round(2 / (2 - f_skip), 4),
                    "skip_efficiency_eta": round((1.0 - ms / ms_dense) / (f_skip / 2.0), 4) if f_skip > 0 else None}
+            if want_sclk:
+                mhz = sclk(thr_d)
+                rec["sclk_mhz_under_load"] = mhz
+                if mhz:     # the same executed rate against the matrix peak at the clock the chip actually held
+                    rec["mfma_frac_at_observed_clock"] = round(rec["mfma_frac_executed"] * NOMINAL_SCLK_MHZ / mhz, 4)
             if not args.no_cpu:
                 rep, _, t_cpu, _ = check(thr, thr_d, parity_budget, 1)
                 rec["parity"] = {"items": rep.n_items, "max_abs": rep.max_abs, "mean_abs": rep.mean_abs,
@@ -174,7 +200,7 @@ def main():
         return ctx, points
 
     # ---- headline size: dense, --skip, sweep -----------------------------------------------------
-    ctx, pts = measure(args.seqlen, [args.skip] + sweep_targets, args.steps, args.warmup, 1.5e5)
+    ctx, pts = measure(args.seqlen, [args.skip] + sweep_targets, args.steps, args.warmup, 1.5e5, want_sclk=True)
     if args.copy_probe:
         torch.add(ctx["q"], 0, out=ctx["out"])
         torch.cuda.synchronize()
@@ -201,7 +227,10 @@ def main():
                    "seqlen": shp.seqlen, "target_skip": args.skip, "forward_workspace": not args.no_workspace},
         "skip_fraction_of_reachable": head["skip_fraction_of_reachable"], "skip_fraction_of_gateable": head["skip_fraction_of_gateable"],
         "dense_path": {"ms_per_step": dense["ms_per_step"], "tflops": dense["dense_equiv_tflops"],
-                       "mfma_frac_executed": dense["mfma_frac_executed"]},
+                       "mfma_frac_executed": dense["mfma_frac_executed"],
+                       "sclk_mhz_under_load": dense.get("sclk_mhz_under_load"),
+                       "mfma_frac_at_observed_clock": dense.get("mfma_frac_at_observed_clock")},
+        "sclk_mhz_under_load": head.get("sclk_mhz_under_load"),
         "speedup_vs_own_dense": head["speedup_vs_own_dense"], "ideal_speedup": head["ideal_speedup"],
         "skip_efficiency_eta": head["skip_efficiency_eta"],
         "step_ms_min_median": head["step_ms_min_median"],
@@ -240,6 +269,35 @@ def main():
             result["sizes"].append({"seqlen": n, "dense": p2[0], "gated": p2[1], "calibrate_s": round(c2["t_calib"], 3)})
             del c2
             torch.cuda.empty_cache()
+    # ---- what the matrix pipe sustains on this card, with nothing else running --------------------
+    # (the published peak assumes the nominal clock; under dense matrix load the chip clocks down, by an
+    # amount that depends on the operand values, so the ceiling is measured with the workload's distribution)
+    if not args.no_mfma_probe:
+        wgs = torch.cuda.get_device_properties(dev).multi_processor_count * 8
+        g = torch.Generator(device="cpu").manual_seed(7)
+        sink = torch.empty(binding.lib().bsfa_mfma_rate_probe_sink_bytes(wgs) // 4, dtype=torch.float32, device=dev)
+        probe = {"workgroups": wgs, "threads_per_workgroup": 512, "instruction": "v_mfma_f32_32x32x16_bf16"}
+        for name, ops in (("constant_operands_tflops", torch.full((4096,), 1.0e-3)),
+                          ("normal_operands_tflops", torch.randn(4096, generator=g))):
+            ops = ops.to(dev)
+            binding.mfma_rate_probe(ops, wgs, 2000, sink)
+            torch.cuda.synchronize()
+            rates = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fl = binding.mfma_rate_probe(ops, wgs, 20000, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                rates.append(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+            probe[name] = round(float(np.median(rates)), 1)
+        probe["note"] = ("back-to-back MFMAs only, two waves per SIMD; 'normal' fills the operand registers with N(0,1) "
+                         "samples (the workload's distribution), 'constant' with one small value")
+        result["sustained_mfma"] = probe
+        sus = probe["normal_operands_tflops"]
+        result["dense_path"]["frac_of_sustained_mfma"] = round(dense["executed_tflops"] / sus, 4)
+        result["roofline"]["frac_of_sustained_mfma"] = round(result["roofline"]["achieved"] / sus, 4)
+        del sink
     # ---- score product on fp8 operands (qk_fp8 = 1): dense and --skip at the headline length ------------
     if not args.no_fp8_leg and bm == 128:
         c4, p4 = measure(args.seqlen, [args.skip], args.steps, args.warmup, 1.0e5, qk_fp8=True)

@@ -222,6 +222,26 @@ size_t bsfa_calibrate_workspace_bytes(const bsfa_problem *p);
  * (block_m, block_n, head_dim) triples and returns the number of supported triples. */
 int bsfa_query_build(int32_t *block_m, int32_t *block_n, int32_t *head_dim, int cap);
 
+/*
+ * Measurement utility, not an operation of the paper: enqueues one kernel in which every wave of
+ * `workgroups` workgroups (512 threads each: two waves per SIMD, the occupancy of bsfa_forward) issues
+ * 16 * iters back-to-back 32x32x16 bf16 matrix instructions whose operand registers are filled from
+ * `operands`, and nothing else.  Timed with events on hip_stream, bsfa_mfma_rate_probe_flops(workgroups,
+ * iters) / time is the matrix rate the card sustains for those operand VALUES: the chip lowers its shader
+ * clock under dense matrix load, and how far depends on how much the operand bits toggle, so this rate --
+ * not the published peak, which assumes the nominal clock -- is what a kernel built on the same
+ * instruction can approach.  bench.py reports it beside the roofline figures.
+ *   operands DEVICE [4096] floats (converted to bf16 in the kernel)
+ *   sink     DEVICE, at least bsfa_mfma_rate_probe_sink_bytes(workgroups) bytes; receives the
+ *            accumulators' sums (only there so that the work is not optimised away)
+ * Errors: BSFA_ERR_NULL, BSFA_ERR_SHAPE (workgroups outside [1, 2^20] or iters < 1), BSFA_ERR_WORKSPACE
+ * (sink too small), BSFA_ERR_HIP.  Nothing is launched on an error.
+ */
+bsfa_status bsfa_mfma_rate_probe(const float *operands, float *sink, size_t sink_bytes, int workgroups, int iters,
+                                 void *hip_stream);
+size_t bsfa_mfma_rate_probe_sink_bytes(int workgroups);
+double bsfa_mfma_rate_probe_flops(int workgroups, int iters);
+
 const char *bsfa_status_string(bsfa_status s);
 const char *bsfa_last_error(void); /* thread-local, valid until the next failing call */
 

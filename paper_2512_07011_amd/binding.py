@@ -20,6 +20,7 @@ STATUS_NAMES = {0: "BSFA_OK", -1: "BSFA_ERR_NULL", -2: "BSFA_ERR_SHAPE", -3: "BS
 EXPORTS = ["bsfa_forward", "bsfa_forward_workspace_bytes", "bsfa_calibrate", "bsfa_calibrate_noalloc",
            "bsfa_calibrate_noalloc_max_values", "bsfa_calibrate_topk",
            "bsfa_calibrate_workspace_bytes", "bsfa_query_build",
+           "bsfa_mfma_rate_probe", "bsfa_mfma_rate_probe_sink_bytes", "bsfa_mfma_rate_probe_flops",
            "bsfa_status_string", "bsfa_last_error"]
 
 
@@ -90,6 +91,12 @@ def lib() -> ctypes.CDLL:
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.bsfa_query_build.restype = ctypes.c_int
         L.bsfa_query_build.argtypes = [i32p, i32p, i32p, ctypes.c_int]
+        L.bsfa_mfma_rate_probe.restype = ctypes.c_int
+        L.bsfa_mfma_rate_probe.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp]
+        L.bsfa_mfma_rate_probe_sink_bytes.restype = ctypes.c_size_t
+        L.bsfa_mfma_rate_probe_sink_bytes.argtypes = [ctypes.c_int]
+        L.bsfa_mfma_rate_probe_flops.restype = ctypes.c_double
+        L.bsfa_mfma_rate_probe_flops.argtypes = [ctypes.c_int, ctypes.c_int]
         L.bsfa_status_string.restype = ctypes.c_char_p
         L.bsfa_status_string.argtypes = [ctypes.c_int]
         L.bsfa_last_error.restype = ctypes.c_char_p
@@ -275,6 +282,21 @@ def bsfa_calibrate_noalloc(q: torch.Tensor, k: torch.Tensor, target_skip_fractio
     _check(lib().bsfa_calibrate_noalloc(ctypes.byref(p), q.data_ptr(), k.data_ptr(), int(bool(causal)), fr, n,
                                         thresholds_out.data_ptr(), ctypes.c_void_p(s.cuda_stream)))
     return thresholds_out
+
+
+def mfma_rate_probe(operands: torch.Tensor, workgroups: int, iters: int, sink: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> float:
+    """Enqueues the matrix-instruction rate probe (measurement utility) on ``operands`` (4096 float32 values on
+    the GPU) and returns the floating-point operations it performs; the caller times it with events."""
+    if not operands.is_cuda or operands.dtype != torch.float32 or not operands.is_contiguous() or operands.numel() < 4096:
+        raise TypeError("mfma_rate_probe: operands must be a contiguous float32 GPU tensor of at least 4096 values")
+    need = lib().bsfa_mfma_rate_probe_sink_bytes(int(workgroups))
+    if sink is None:
+        sink = torch.empty(max(need, 4) // 4, dtype=torch.float32, device=operands.device)
+    s = stream if stream is not None else torch.cuda.current_stream(operands.device)
+    _check(lib().bsfa_mfma_rate_probe(operands.data_ptr(), sink.data_ptr(), sink.numel() * sink.element_size(),
+                                      int(workgroups), int(iters), ctypes.c_void_p(s.cuda_stream)))
+    return float(lib().bsfa_mfma_rate_probe_flops(int(workgroups), int(iters)))
 
 
 def bsfa_calibrate_topk(samples, ks: Sequence[int], causal: bool = True, block_m: int = 128, block_n: int = 64,

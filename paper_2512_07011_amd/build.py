@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbsfa.so")
-SOURCES = ["bsfa_fwd.hip", "bsfa_select.hip", "bsfa_api.hip"]
+SOURCES = ["bsfa_fwd.hip", "bsfa_select.hip", "bsfa_probe.hip", "bsfa_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are kept out of the generated code on this target

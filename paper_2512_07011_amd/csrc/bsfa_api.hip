@@ -388,4 +388,29 @@ const char *bsfa_status_string(bsfa_status s)
 
 const char *bsfa_last_error(void) { return g_err; }
 
+size_t bsfa_mfma_rate_probe_sink_bytes(int workgroups)
+{
+    return workgroups > 0 ? (size_t)workgroups * bsfa::kProbeThreads * sizeof(float) : 0;
+}
+
+double bsfa_mfma_rate_probe_flops(int workgroups, int iters)
+{
+    if (workgroups <= 0 || iters <= 0) return 0.0;
+    return (double)workgroups * (bsfa::kProbeThreads / 64) * (double)iters * bsfa::kProbeMfmaPerIter * (2.0 * 32 * 32 * 16);
+}
+
+bsfa_status bsfa_mfma_rate_probe(const float *operands, float *sink, size_t sink_bytes, int workgroups, int iters,
+                                 void *hip_stream)
+{
+    if (!operands || !sink) return fail(BSFA_ERR_NULL, "bsfa_mfma_rate_probe: operands and sink are required");
+    if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20))
+        return fail(BSFA_ERR_SHAPE, "bsfa_mfma_rate_probe: workgroups in [1, 2^20] and iters > 0 expected");
+    if (sink_bytes < bsfa_mfma_rate_probe_sink_bytes(workgroups))
+        return fail(BSFA_ERR_WORKSPACE, "bsfa_mfma_rate_probe: sink holds %zu bytes, %zu needed", sink_bytes,
+                    bsfa_mfma_rate_probe_sink_bytes(workgroups));
+    const hipError_t e = bsfa::launch_mfma_rate_probe(operands, sink, workgroups, iters, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(BSFA_ERR_HIP, "bsfa_mfma_rate_probe: %s", hipGetErrorString(e));
+    return BSFA_OK;
+}
+
 }  // extern "C"

@@ -55,4 +55,10 @@ size_t select_area_bytes(int hq);
 hipError_t launch_select(const float *dump, long per_head, int batch, int hq, const SelectLevels &lv, int n_levels,
                          void *area, float *out_dev, hipStream_t stream);
 
+// ---- matrix-instruction rate probe (bsfa_probe.hip) --------------------------------------------
+constexpr int kProbeThreads = 512;        // 8 waves per workgroup: two per SIMD, as the forward kernel runs
+constexpr int kProbeMfmaPerIter = 16;     // 32x32x16 MFMAs per wave and iteration
+// operands: DEVICE, 4096 floats; sink: DEVICE, workgroups * kProbeThreads floats.  Enqueues one kernel.
+hipError_t launch_mfma_rate_probe(const float *operands, float *sink, int workgroups, int iters, hipStream_t stream);
+
 }  // namespace bsfa
