@@ -45,6 +45,8 @@ def main():
                     help="comma-separated extra sequence lengths timed at --skip and dense ('' for none): adds a 'sizes' list")
     ap.add_argument("--noncausal", type=int, default=32768,
                     help="sequence length of the bidirectional leg (causal = 0; dense and --skip); 0 for none")
+    ap.add_argument("--no-sclk", action="store_true",
+                    help="do not sample the shader clock under load (it runs extra launches outside the timed region)")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the probe of the matrix rate the card sustains (back-to-back MFMAs, nothing else)")
     ap.add_argument("--no-fp8-leg", action="store_true",
@@ -200,7 +202,7 @@ def main():
         return ctx, points
 
     # ---- headline size: dense, --skip, sweep -----------------------------------------------------
-    ctx, pts = measure(args.seqlen, [args.skip] + sweep_targets, args.steps, args.warmup, 1.5e5, want_sclk=True)
+    ctx, pts = measure(args.seqlen, [args.skip] + sweep_targets, args.steps, args.warmup, 1.5e5, want_sclk=not args.no_sclk)
     if args.copy_probe:
         torch.add(ctx["q"], 0, out=ctx["out"])
         torch.cuda.synchronize()
