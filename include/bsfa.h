@@ -129,7 +129,10 @@ typedef struct {
     uint32_t *skip_mask;  /* [batch][n_q_heads][M_Q][ceil(M_KV/32)], bit (j%32) of word j/32
                              set iff block j was skipped for query tile i */
     float    *block_max;  /* [batch][n_q_heads][M_Q][M_KV]: s_max (Eq. 6, natural score units,
-                             1/sqrt(d) included) of gateable blocks, NaN elsewhere */
+                             1/sqrt(d) included) of gateable blocks, NaN elsewhere.  A diagnostic: asking
+                             for it makes every key block take the kernel's general stages, which exchange
+                             the maxima themselves instead of the waves' keep flags (a few per cent slower);
+                             counts, skip_mask and lse cost nothing measurable. */
     float    *lse;        /* [batch][seqlen][n_q_heads]: L = m + log(l) over the kept blocks, natural
                              units (last line of Algorithm 1; what a backward pass or a merge of
                              partial results over key ranges needs) */

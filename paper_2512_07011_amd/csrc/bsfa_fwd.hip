@@ -16,13 +16,16 @@
 // Software pipeline, one barrier per key block.  The scores of block j+1 are computed while block
 // j is finished, so the gate decision is known one block ahead:
 //   stage j:  softmax(S_j) -> P_j          (VALU) interleaved with
-//             S_{j+1} = K_{j+1} Q^T        (MFMA); block max of S_{j+1} -> LDS
+//             S_{j+1} = K_{j+1} Q^T        (MFMA); per-lane maximum of S_{j+1}; the wave's keep flag
+//             (or, in the general stages, its block maximum) -> LDS
 //             wait for the copies needed next; barrier
-//             O^T += V_j^T P_j^T           (MFMA), and a few MFMAs into it:
-//             decide keep_{j+1}; request V_{j+1} (only if kept) and K_{j+KR+1}
+//             O^T += V_j^T P_j^T           (MFMA), and between those MFMAs, a few instructions at a
+//             time: decide keep_{j+1}; request V_{j+1} (only if kept) and K_{j+KR+1}; running
+//             maximum of block j+1; first score operands of block j+2
 // K tiles sit in a ring of KR LDS slots and are requested KR+1 blocks ahead, V tiles in two slots;
 // both go HBM -> LDS directly, and the waits are partial (vmcnt) so that only the tile needed
-// next has to have landed.
+// next has to have landed.  With a workspace V arrives pre-transposed (transpose_v_kernel) and its
+// operand is a plain 16-byte LDS read; without one it is gathered with the transposing read.
 #include "bsfa_dev.h"
 
 namespace bsfa {
