@@ -177,3 +177,72 @@ def test_sampled_parity_at_256k():
     rep = parity.compare(q, k, v, tau, 128, 64, True, out, st.skip_mask, None, items=items)
     print("N=%d: max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips" % (n, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
     assert rep.skipped > 0
+
+
+def test_flag_gate_and_maximum_gate_agree_32k():
+    """The fast stages decide from per-wave keep flags, the general stages (taken by every block when
+    the block maxima are requested) from the exchanged maxima: same decisions, same output, bit for
+    bit, and the dumped maxima reproduce every decision (skip iff s_max < T, Section 4.1)."""
+    n = 32768
+    shp, (qc, kc, _) = gen(n, 1)
+    tau = binding.bsfa_calibrate(qc, kc, [0.5])[0]
+    del qc, kc
+    shp, (q, k, v) = gen(n, 0)
+    s_flag = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True, lse=True)
+    s_max = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True, block_max=True, lse=True)
+    o_flag = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=s_flag).clone()
+    o_max = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=s_max)
+    torch.cuda.synchronize()
+    assert torch.equal(s_flag.counts, s_max.counts)
+    assert torch.equal(s_flag.skip_mask, s_max.skip_mask)
+    assert torch.equal(o_flag.view(torch.int16), o_max.view(torch.int16))
+    assert torch.equal(s_flag.lse, s_max.lse)
+    # decisions from the dumped maxima, for a few heads (host side, vectorised)
+    for h in (0, 13, 31):
+        bmax = s_max.block_max[0, h].cpu().numpy()                       # [M_Q, M_KV], NaN = not gateable
+        words = s_max.skip_mask[0, h].cpu().numpy()
+        skipped = parity.unpack_mask(words[None, None], shp.m_kv)[0, 0]
+        gate = ~np.isnan(bmax)
+        assert not (skipped & ~gate).any()
+        assert (skipped[gate] == (bmax[gate] < float(tau[h]))).all()
+
+
+def test_noncausal_sampled_parity_32k():
+    """Bidirectional attention in the benchmarked configuration: the fused stages run before and behind
+    the tile's own token range (Section 4.3, last sentence); sampled items against the oracle."""
+    n = 32768
+    shp, (qc, kc, _) = gen(n, 1)
+    tau = binding.bsfa_calibrate(qc, kc, [0.5], causal=False)[0]
+    del qc, kc
+    shp, (q, k, v) = gen(n, 0)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV), causal=False, skip_stats=st)
+    torch.cuda.synchronize()
+    c = st.counts.cpu().numpy()[0]
+    assert (c[:, 2] == shp.m_q * shp.m_kv).all() and (c[:, 1] == shp.m_q * (shp.m_kv - 2)).all()
+    assert abs(c[:, 0].sum() / c[:, 1].sum() - 0.5) < 0.05
+    items = [(0, 0, 0), (0, 7, 1), (0, 12, 100), (0, 21, shp.m_q // 2), (0, 30, shp.m_q - 2), (0, 31, shp.m_q - 1)]
+    rep = parity.compare(q, k, v, tau, 128, 64, False, out, st.skip_mask, None, items=items)
+    print("non-causal N=%d: max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips" % (n, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
+    assert rep.skipped > 0
+
+
+def test_fp8_score_product_sampled_parity_32k():
+    """qk_fp8 in the benchmarked configuration: thresholds calibrated in the same mode; the oracle gets Q
+    and K rounded to e4m3 (what the score product multiplies) and the ordinary tolerances apply."""
+    n = 32768
+    shp, (qc, kc, _) = gen(n, 1)
+    tau = binding.bsfa_calibrate(qc, kc, [0.5], qk_fp8=True)[0]
+    del qc, kc
+    shp, (q, k, v) = gen(n, 0)
+    st = binding.alloc_stats(q, 128, 64, counts=True, skip_mask=True)
+    out = binding.bsfa_forward(q, k, v, tau.to(DEV), skip_stats=st, qk_fp8=True)
+    torch.cuda.synchronize()
+    c = st.counts.cpu().numpy()[0]
+    assert abs(c[:, 0].sum() / c[:, 1].sum() - 0.5) < 0.05
+    q8, k8 = (t.to(torch.float8_e4m3fn).to(torch.bfloat16) for t in (q, k))
+    items = parity.sample_items(shp, n_random=1, seed=8)[::3]
+    rep = parity.compare(q8, k8, v, tau, 128, 64, True, out, st.skip_mask, None, items=items)
+    print("fp8 QK N=%d: %d items, max_abs %.3g mean_abs %.3g, %d in-band tiles, %d flips"
+          % (n, rep.n_items, rep.max_abs, rep.mean_abs, rep.in_band, rep.mask_mismatch))
+    assert rep.skipped > 0
