@@ -210,7 +210,8 @@ size_t bsfa_calibrate_noalloc_max_values(void);
  *                  sequence, with threshold_tiles = this M_Q)
  *   workspace      DEVICE, at least bsfa_calibrate_workspace_bytes(p) bytes
  * p->thresholds_per_tile and p->threshold_tiles are ignored; p->seqlens must be NULL (samples of
- * one call have one length).  Synchronises hip_stream.
+ * one call have one length); p->gate_mode and p->qk_fp8 must be 0 (BSFA_ERR_UNSUPPORTED otherwise).
+ * Synchronises hip_stream.
  */
 bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void *k, int causal,
                                 const int32_t *ks, int n_levels, int samples_done,

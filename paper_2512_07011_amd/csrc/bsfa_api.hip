@@ -299,9 +299,9 @@ bsfa_status bsfa_calibrate_noalloc(const bsfa_problem *p, const void *q, const v
                                         "(use bsfa_calibrate with a workspace)", values, kScratchDumpBytes / sizeof(float));
     if (p->n_q_heads > kScratchMaxHeads)
         return fail(BSFA_ERR_WORKSPACE, "n_q_heads = %d exceeds the %d the built-in scratch array is sized for", p->n_q_heads, kScratchMaxHeads);
+    if (p->qk_fp8) return fail(BSFA_ERR_UNSUPPORTED, "qk_fp8 is not available without a workspace (use bsfa_calibrate)");
     unsigned char *base = scratch_address();
     if (!base) return BSFA_ERR_HIP;
-    if (p->qk_fp8) return fail(BSFA_ERR_UNSUPPORTED, "qk_fp8 is not available without a workspace (use bsfa_calibrate)");
     return calibrate_on_device(p, q, k, causal, target_skip_fractions, n_levels, reinterpret_cast<float *>(base),
                                base + kScratchDumpBytes, thresholds_out_device, nullptr, static_cast<hipStream_t>(hip_stream));
 }
@@ -314,6 +314,7 @@ bsfa_status bsfa_calibrate_topk(const bsfa_problem *p, const void *q, const void
     if (s != BSFA_OK) return s;
     if (p->seqlens) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate_topk takes samples of one length (seqlens must be NULL)");
     if (p->gate_mode) return fail(BSFA_ERR_UNSUPPORTED, "calibration is defined for the block-maximum gate (gate_mode 0) only");
+    if (p->qk_fp8) return fail(BSFA_ERR_UNSUPPORTED, "bsfa_calibrate_topk runs the 16-bit score product only (qk_fp8 must be 0)");
     if (!q || !k || !ks || !thresholds_out) return fail(BSFA_ERR_NULL, "q, k, ks and thresholds_out must be non-NULL");
     if (n_levels < 1) return fail(BSFA_ERR_SHAPE, "n_levels must be positive");
     if (samples_done < 0) return fail(BSFA_ERR_SHAPE, "samples_done must be non-negative");
