@@ -571,12 +571,16 @@ __global__ void __launch_bounds__(NWH * HP * 64, 2) bsfa_fwd_kernel(const FwdPar
                 });
             }
         } else {
+            // the operand reads first, so that they travel while the look-ahead is issued (where V is
+            // gathered in place the registers do not allow it: there they come last)
+            if constexpr (VT || CALIB) prefetch_k(lds_k0 + kring);
+            __builtin_amdgcn_sched_barrier(0);
             la_decide();
-            la_stats();
+            la_softmax();
             la_vcopy();
             la_kcopy();
-            la_softmax();
-            prefetch_k(lds_k0 + kring);
+            la_stats();
+            if constexpr (!(VT || CALIB)) prefetch_k(lds_k0 + kring);
         }
     };
 
